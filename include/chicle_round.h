@@ -1,0 +1,181 @@
+/*
+ * chicle_round.h - C ABI of the CoCoA round for generalised linear models on one MI355X.
+ *
+ * One round (paper Section 2.2 "CoCoA", Eq. 1 and Eq. 2; trainer/solver protocol of
+ * Section 4.1-4.2; Section 5.1 "CoCoA" for the hyper-parameters) is
+ *
+ *     K local solvers each make one stochastic-coordinate pass (L = 1, H = all local samples)
+ *     over the rows of the data chunks they own, starting from the shared vector w
+ *  -> their updates Delta w_k are combined into w (adding; sigma = K makes the plain sum safe)
+ *  -> the duality gap P(w) - D(alpha) is evaluated.
+ *
+ * Problem solved:   P(w) = lambda/2 |w|^2 + 1/n sum_i loss_i(x_i . w)
+ *                   D(a) = -lambda/2 |w(a)|^2 - 1/n sum_i loss_i^*(-a_i),  w(a) = 1/(lambda n) sum_i a_i s_i x_i
+ *   hinge   : loss_i(z) = max(0, 1 - y_i z), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]
+ *   squared : loss_i(z) = (z - y_i)^2 / 2,  s_i = 1,  a_i real
+ *
+ * Data live in HBM as chunks (Section 3 "Uni-tasks", Section 4.4 "In-memory chunk data
+ * format"): a chunk is one contiguous block holding a run of rows (CSR or dense) together with
+ * its per-row state (label, dual variable alpha, squared norm).  Chunks are the unit that the
+ * scheduler hands to solvers; the state always stays inside its chunk.  The ownership contract
+ * of Section 3 is enforced as a state machine:
+ *
+ *     LOADING --assign--> READY --local_epoch--> EPOCH_DONE --aggregate--> READY
+ *
+ *   - between iterations (READY, LOADING) the scheduler owns the chunks: load, assign, set_alpha,
+ *     set_w are legal;
+ *   - during an iteration (EPOCH_DONE: the solvers' updates are not merged yet) they are not.
+ *
+ * Conventions
+ *   - every function returns CHICLE_OK (0) or a negative chicle_status; nothing throws or aborts;
+ *     chicle_last_error() gives a message for the last failure on that context;
+ *   - "host" pointers are ordinary CPU memory, read or written before the call returns; the caller
+ *     keeps ownership;  "device" pointers are HBM addresses valid on the context's GPU;
+ *   - the library allocates no device memory: it carves everything out of the arena handed to
+ *     chicle_create (size it with chicle_arena_bytes); the arena and the HIP stream are borrowed for
+ *     the lifetime of the context; all work is enqueued on that stream;
+ *   - calls that return values to the host (gap, get_*) wait for the stream; the others only enqueue;
+ *   - a context is not thread-safe.
+ */
+#ifndef CHICLE_ROUND_H
+#define CHICLE_ROUND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct chicle_ctx chicle_ctx;
+
+enum chicle_status {
+    CHICLE_OK = 0,
+    CHICLE_EINVAL = -1,   /* bad argument, malformed chunk, bad table */
+    CHICLE_ENOMEM = -2,   /* arena too small */
+    CHICLE_ESTATE = -3,   /* call not legal in the current state (ownership contract) */
+    CHICLE_EDEVICE = -4   /* HIP error, or a kernel flagged bad input (e.g. perm entry out of range) */
+};
+
+enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1 };
+
+/* Which local-solver kernel chicle_local_epoch launches (both visit the coordinates in exactly the
+ * given order; they differ only in floating-point summation order). */
+enum chicle_solver_kind {
+    CHICLE_SOLVER_AUTO = 0,       /* choose from the data shape */
+    CHICLE_SOLVER_ROWWISE = 1,    /* one coordinate step at a time */
+    CHICLE_SOLVER_BATCHED = 2     /* blocks of rows via their Gram matrix, same sequence of steps */
+};
+
+/* Timed segments reported by chicle_last_kernel_ms. */
+enum chicle_segment {
+    CHICLE_SEG_LOCAL_EPOCH = 0,   /* everything chicle_local_epoch enqueued */
+    CHICLE_SEG_AGGREGATE = 1,
+    CHICLE_SEG_GAP = 2,
+    CHICLE_SEG_EPOCH_GRAM = 3,    /* batched solver only: the Gram-block kernel */
+    CHICLE_SEG_EPOCH_CHAIN = 4,   /* the kernel that runs the coordinate steps */
+    CHICLE_SEG_COUNT = 5
+};
+
+/* Bytes of device arena a context needs (host, pure).  total_entries = stored matrix entries over all
+ * chunks (CSR non-zeros, or n_total*d for dense chunks).  Returns 0 on bad arguments. */
+size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int32_t n_chunks,
+                          int32_t max_solvers, int32_t dense);
+
+/* Create a context in state LOADING with alpha = 0, w = 0.
+ *   loss          chicle_loss
+ *   n_total       number of rows over all chunks (the n of the objective)
+ *   d             number of columns (length of w)
+ *   lambda        normalised regulariser (> 0)
+ *   n_chunks      chunk ids are 0 .. n_chunks-1
+ *   max_solvers   largest K that will ever be assigned
+ *   dense         1: all chunks dense row-major, 0: all chunks CSR
+ *   device_arena  device pointer, 256-byte aligned, arena_bytes long, borrowed
+ *   hip_stream    hipStream_t (NULL = the default stream), borrowed
+ * Errors: EINVAL (arguments), ENOMEM (arena smaller than chicle_arena_bytes), EDEVICE. */
+int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, double lambda,
+                  int32_t n_chunks, int32_t max_solvers, int32_t dense, int64_t total_entries,
+                  void *device_arena, size_t arena_bytes, void *hip_stream);
+
+/* Copy one chunk into the chunk store (Section 4.4).  All pointers are host arrays.
+ *   row_ptr  n_rows+1 chunk-local offsets, row_ptr[0] = 0, non-decreasing
+ *   col      row_ptr[n_rows] column ids in [0, d), strictly ascending inside a row
+ *   val      matching values;  y  n_rows labels (+-1 for hinge) or targets
+ *   alpha0   initial dual variables or NULL for zeros (hinge: must lie in [0,1])
+ * Legal in LOADING only.  Errors: EINVAL (malformed arrays, id out of range or already loaded,
+ * hinge label not +-1), ENOMEM (store full), ESTATE. */
+int chicle_load_chunk_csr(chicle_ctx *ctx, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
+                          const int32_t *col, const float *val, const float *y, const float *alpha0);
+
+/* Dense variant: X is row-major n_rows x d (host). */
+int chicle_load_chunk_dense(chicle_ctx *ctx, int32_t chunk_id, int32_t n_rows, const float *X,
+                            const float *y, const float *alpha0);
+
+/* Greedy balanced chunk -> solver table (host, pure, integers only): chunks by (load descending, id
+ * ascending), each to the solver that would finish it earliest, (L_k + load)/speed_k, ties to the
+ * smallest solver index.  speed_q: K positive integer speed weights or NULL for equal speeds.
+ * This is the elastic-scaling / load-balancing step of Section 3 reduced to one deterministic rule
+ * (the paper's policies of Section 4.5 pick chunks randomly or shift them gradually). */
+int chicle_balance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const int32_t *speed_q,
+                   int32_t *chunk_to_solver_out);
+
+/* Scheduler step between iterations: give every chunk to one of K solvers (host table of n_chunks
+ * entries in [0, K)); sigma becomes K; every solver's private vector is re-seeded with w.  A solver
+ * may own no chunk.  alpha is not touched.  A solver's local rows are its chunks in ascending chunk id,
+ * rows ascending inside a chunk.  Legal in LOADING (all chunks loaded, row counts summing to n_total)
+ * and READY.  Errors: EINVAL, ESTATE. */
+int chicle_assign(chicle_ctx *ctx, int32_t K, const int32_t *chunk_to_solver);
+
+/* Rows owned by each solver under the current assignment (host out, K entries). */
+int chicle_solver_rows(chicle_ctx *ctx, int64_t *rows_out);
+
+/* Select the local-solver kernel (chicle_solver_kind); default AUTO. */
+int chicle_set_solver(chicle_ctx *ctx, int32_t kind);
+
+/* One local pass of all K solvers, concurrently, each from the current w (Section 2.2; Section 4.2).
+ * perm_device: device array of n_total int32: solver 0's visiting order (a permutation of
+ * [0, rows_0)), then solver 1's, and so on.  Commits alpha in the chunks and leaves
+ * v_k = w + sigma * Delta w_k in each solver's private vector.  READY -> EPOCH_DONE.
+ * An out-of-range perm entry is skipped and reported as EDEVICE by the next synchronising call. */
+int chicle_local_epoch(chicle_ctx *ctx, const int32_t *perm_device);
+
+/* Same with the orders given as a host array (copied to a staging area first). */
+int chicle_local_epoch_host_perm(chicle_ctx *ctx, const int32_t *perm_host);
+
+/* Trainer step (Section 4.1: merge updates, broadcast the model): w <- w + sum_k Delta w_k, then every
+ * private vector <- w.  EPOCH_DONE -> READY. */
+int chicle_aggregate(chicle_ctx *ctx);
+
+/* P(w), D(alpha) and P - D at the current state (host outs, any may be NULL).  Legal in READY.
+ * Synchronises. */
+int chicle_gap(chicle_ctx *ctx, double *primal, double *dual, double *gap);
+
+/* State access (host arrays of d floats / n_rows-of-that-chunk floats).  get_* synchronise.
+ * set_w and set_alpha are legal in READY/LOADING only; get_delta_w in EPOCH_DONE only:
+ * solver >= 0 gives Delta w_solver = (v_solver - w)/sigma, solver = -1 gives sum_k Delta w_k. */
+int chicle_get_w(chicle_ctx *ctx, float *w_out);
+int chicle_set_w(chicle_ctx *ctx, const float *w_in);
+int chicle_get_delta_w(chicle_ctx *ctx, int32_t solver, float *dw_out);
+int chicle_get_alpha(chicle_ctx *ctx, int32_t chunk_id, float *alpha_out);
+int chicle_set_alpha(chicle_ctx *ctx, int32_t chunk_id, const float *alpha_in);
+int chicle_get_assignment(chicle_ctx *ctx, int32_t *chunk_to_solver_out, int32_t *K_out);
+
+/* Device address of w (d floats), for callers that keep everything on the GPU. */
+int chicle_w_device(chicle_ctx *ctx, const float **w_device_out);
+
+/* Wait for the stream; report any deferred kernel error. */
+int chicle_sync(chicle_ctx *ctx);
+
+/* Event timing of the library's own launches.  With profiling on, every call records HIP events on the
+ * context's stream around each segment; chicle_last_kernel_ms waits for the segment's end event and
+ * returns the duration of its most recent execution in milliseconds. */
+int chicle_set_profiling(chicle_ctx *ctx, int32_t on);
+int chicle_last_kernel_ms(chicle_ctx *ctx, int32_t segment, float *ms_out);
+
+const char *chicle_last_error(chicle_ctx *ctx);
+void chicle_destroy(chicle_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHICLE_ROUND_H */

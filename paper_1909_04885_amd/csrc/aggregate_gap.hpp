@@ -1,0 +1,196 @@
+// Trainer-side kernels: merge of the solvers' updates (paper Section 4.1: "merge updates, broadcast
+// model") and the duality gap that solvers report as convergence metric (Section 4.1, Section 5.1).
+#pragma once
+#include <hip/hip_runtime.h>
+#include "device_types.hpp"
+#include "sdca_rowwise.hpp"
+
+namespace chicle {
+
+// v_k <- w for k < K (a solver fetching the model).
+__global__ __launch_bounds__(256) void seed_private(const float *__restrict__ w, float *v_all,
+                                                    int64_t ld_v, int64_t d, int K)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
+        const float x = w[j];
+        for (int k = 0; k < K; ++k) v_all[(int64_t)k * ld_v + j] = x;
+    }
+}
+
+// w <- w + sum_k Delta w_k with Delta w_k = (v_k - w)/sigma, then v_k <- w for all k.
+// One pass: reads K + 1 vectors, writes K + 1 vectors, four columns per thread (ld_v and the
+// buffers are 16-byte aligned; d is handled up to its padded length, the padding holds zeros).
+__global__ __launch_bounds__(256) void aggregate_broadcast(float *w, float *v_all, int64_t ld_v,
+                                                           int64_t d4, int K, float inv_sigma)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    float4 *w4 = reinterpret_cast<float4 *>(w);
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d4; j += stride) {
+        const float4 x = w4[j];
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < K; ++k) {
+            const float4 vk = reinterpret_cast<const float4 *>(v_all + (int64_t)k * ld_v)[j];
+            acc.x += vk.x - x.x; acc.y += vk.y - x.y; acc.z += vk.z - x.z; acc.w += vk.w - x.w;
+        }
+        float4 o;
+        o.x = x.x + acc.x * inv_sigma; o.y = x.y + acc.y * inv_sigma;
+        o.z = x.z + acc.z * inv_sigma; o.w = x.w + acc.w * inv_sigma;
+        w4[j] = o;
+        for (int k = 0; k < K; ++k) reinterpret_cast<float4 *>(v_all + (int64_t)k * ld_v)[j] = o;
+    }
+}
+
+// out <- Delta w_solver, or sum_k Delta w_k when solver < 0 (read-back helper).
+__global__ __launch_bounds__(256) void delta_w_out(const float *__restrict__ w, const float *v_all,
+                                                   int64_t ld_v, int64_t d, int K, int solver,
+                                                   float inv_sigma, float *out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
+        const float x = w[j];
+        float acc = 0.f;
+        if (solver >= 0) acc = v_all[(int64_t)solver * ld_v + j] - x;
+        else for (int k = 0; k < K; ++k) acc += v_all[(int64_t)k * ld_v + j] - x;
+        out[j] = acc * inv_sigma;
+    }
+}
+
+__device__ __forceinline__ double wave_sum_d(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// Workgroup sum of two doubles -> thread 0 writes them.  256 threads.
+__device__ __forceinline__ void block_sum2_store(double a, double b, double *out_a, double *out_b)
+{
+    __shared__ double ra[4], rb[4];
+    a = wave_sum_d(a);
+    b = wave_sum_d(b);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { ra[wave] = a; rb[wave] = b; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *out_a = ra[0] + ra[1] + ra[2] + ra[3];
+        *out_b = rb[0] + rb[1] + rb[2] + rb[3];
+    }
+}
+
+// Per-row loss and conjugate terms of the gap, sparse rows.  LPR lanes cooperate on one row
+// (LPR divides 64).  Work items are blocks of 256/LPR rows of one chunk; item_prefix[c] = first
+// item of chunk c.  Each workgroup writes one partial (loss sum, conjugate sum) in double.
+//   hinge   : loss = max(0, 1 - y z),   conj = loss^*(-a) = -a
+//   squared : loss = (z - y)^2 / 2,     conj = a^2/2 - a y
+template <int LOSS, int LPR>
+__global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__ chunks,
+                                                    const int32_t *__restrict__ item_prefix,
+                                                    int n_chunks, int total_items,
+                                                    const float *__restrict__ w,
+                                                    double *part_loss, double *part_conj)
+{
+    constexpr int ROWS = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int rloc = threadIdx.x / LPR;
+    double s_loss = 0.0, s_conj = 0.0;
+    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const int c = find_chunk(item_prefix, n_chunks, item);
+        const ChunkDev &ch = chunks[c];
+        const int r = (item - item_prefix[c]) * ROWS + rloc;
+        float z = 0.f;
+        const bool live = r < ch.n_rows;
+        if (live) {
+            const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
+            for (int p = b + sub; p < e; p += LPR) z += ch.val[p] * w[ch.col[p]];
+        }
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
+        if (live && sub == 0) {
+            const float y = ch.y[r], a = ch.alpha[r];
+            if (LOSS == 0) {
+                s_loss += (double)fmaxf(0.f, 1.f - y * z);
+                s_conj += (double)(-a);
+            } else {
+                const float rr = z - y;
+                s_loss += 0.5 * (double)rr * (double)rr;
+                s_conj += 0.5 * (double)a * (double)a - (double)a * (double)y;
+            }
+        }
+    }
+    block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
+}
+
+// Dense rows: one wavefront-quarter (LPR lanes) per row, strided over the d columns.
+template <int LOSS, int LPR>
+__global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks,
+                                                      const int32_t *__restrict__ item_prefix,
+                                                      int n_chunks, int total_items, int d,
+                                                      const float *__restrict__ w,
+                                                      double *part_loss, double *part_conj)
+{
+    constexpr int ROWS = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int rloc = threadIdx.x / LPR;
+    double s_loss = 0.0, s_conj = 0.0;
+    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const int c = find_chunk(item_prefix, n_chunks, item);
+        const ChunkDev &ch = chunks[c];
+        const int r = (item - item_prefix[c]) * ROWS + rloc;
+        float z = 0.f;
+        const bool live = r < ch.n_rows;
+        if (live) {
+            const float *x = ch.val + (int64_t)r * d;
+            for (int p = sub; p < d; p += LPR) z += x[p] * w[p];
+        }
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
+        if (live && sub == 0) {
+            const float y = ch.y[r], a = ch.alpha[r];
+            if (LOSS == 0) {
+                s_loss += (double)fmaxf(0.f, 1.f - y * z);
+                s_conj += (double)(-a);
+            } else {
+                const float rr = z - y;
+                s_loss += 0.5 * (double)rr * (double)rr;
+                s_conj += 0.5 * (double)a * (double)a - (double)a * (double)y;
+            }
+        }
+    }
+    block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
+}
+
+// |w|^2 partials in double.
+__global__ __launch_bounds__(256) void wsq_partial(const float *__restrict__ w, int64_t d,
+                                                   double *part_wsq, double *part_unused)
+{
+    double s = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
+        const double x = (double)w[j];
+        s += x * x;
+    }
+    block_sum2_store(s, 0.0, &part_wsq[blockIdx.x], &part_unused[blockIdx.x]);
+}
+
+// out[0] = sum loss, out[1] = sum conj, out[2] = |w|^2; one workgroup, fixed summation order.
+__global__ __launch_bounds__(256) void gap_finish(const double *part_loss, const double *part_conj,
+                                                  int n_row_parts, const double *part_wsq,
+                                                  int n_w_parts, double *out)
+{
+    double a = 0.0, b = 0.0, c = 0.0;
+    for (int i = threadIdx.x; i < n_row_parts; i += 256) { a += part_loss[i]; b += part_conj[i]; }
+    for (int i = threadIdx.x; i < n_w_parts; i += 256) c += part_wsq[i];
+    __shared__ double ra[4], rb[4], rc[4];
+    a = wave_sum_d(a); b = wave_sum_d(b); c = wave_sum_d(c);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { ra[wave] = a; rb[wave] = b; rc[wave] = c; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        out[0] = ra[0] + ra[1] + ra[2] + ra[3];
+        out[1] = rb[0] + rb[1] + rb[2] + rb[3];
+        out[2] = rc[0] + rc[1] + rc[2] + rc[3];
+    }
+}
+
+}  // namespace chicle

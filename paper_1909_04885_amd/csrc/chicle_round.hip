@@ -1,0 +1,740 @@
+// C ABI of the CoCoA round (see include/chicle_round.h for the contract of every call).
+// Host logic: chunk store carved from a caller-supplied arena, chunk -> solver tables, launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/chicle_round.h"
+#include "aggregate_gap.hpp"
+#include "device_types.hpp"
+#include "sdca_rowwise.hpp"
+
+using namespace chicle;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+constexpr int GAP_PARTS = 4096;        // workgroups (and partial sums) of the gap row kernels
+constexpr int WSQ_PARTS = 512;
+constexpr int MAX_LIST_LDS = 4096;     // chunks one solver may own (its lists are staged in LDS)
+constexpr int DENSE_V_LDS_MAX_D = 8192;
+
+enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
+
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline int64_t pad_d(int64_t d) { return (d + 63) / 64 * 64; }
+
+struct Seg {
+    hipEvent_t start = nullptr, stop = nullptr;
+    bool recorded = false;
+};
+
+}  // namespace
+
+struct chicle_ctx {
+    int loss = 0;
+    int64_t n_total = 0;
+    int32_t d = 0;
+    int64_t ld_v = 0;
+    double lambda = 0;
+    int32_t n_chunks = 0, max_solvers = 0;
+    bool dense = false;
+    int64_t total_entries = 0;
+    char *arena = nullptr;
+    size_t arena_bytes = 0, used = 0;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    State state = ST_LOADING;
+    int solver_kind = CHICLE_SOLVER_AUTO;
+
+    // fixed regions
+    ChunkDev *chunks_dev = nullptr;
+    SolverDev *solvers_dev = nullptr;
+    int32_t *solver_chunks_dev = nullptr, *solver_prefix_dev = nullptr, *item_prefix_dev = nullptr;
+    float *w = nullptr, *v = nullptr, *dw_tmp = nullptr;
+    int32_t *perm_stage = nullptr;
+    double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
+           *gap_out = nullptr;
+    int *err_dev = nullptr;
+
+    // host mirrors
+    std::vector<ChunkDev> chunks;
+    std::vector<char> loaded;
+    int32_t n_loaded = 0;
+    int64_t rows_loaded = 0, entries_loaded = 0;
+    int32_t K = 0;
+    std::vector<int32_t> chunk_to_solver;
+    std::vector<SolverDev> solvers;
+    int max_list = 0;
+    int gap_lpr = 64, gap_items = 0;
+
+    bool profiling = false;
+    Seg seg[CHICLE_SEG_COUNT];
+    std::string err;
+};
+
+namespace {
+
+int fail(chicle_ctx *c, int code, const char *fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return code;
+}
+
+#define HIP_TRY(c, expr)                                                                         \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail((c), CHICLE_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_));            \
+    } while (0)
+
+void *carve(chicle_ctx *c, size_t bytes)
+{
+    const size_t need = align_up(bytes);
+    if (c->used + need > c->arena_bytes) return nullptr;
+    void *p = c->arena + c->used;
+    c->used += need;
+    return p;
+}
+
+size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers)
+{
+    const int64_t ld = pad_d(d);
+    size_t s = 0;
+    s += align_up(sizeof(ChunkDev) * (size_t)n_chunks);
+    s += align_up(sizeof(SolverDev) * (size_t)max_solvers);
+    s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);
+    s += align_up(sizeof(int32_t) * ((size_t)n_chunks + 1));
+    s += align_up(sizeof(float) * (size_t)ld) * 2;                       // w, dw_tmp
+    s += align_up(sizeof(float) * (size_t)ld * (size_t)max_solvers);     // private vectors
+    s += align_up(sizeof(int32_t) * (size_t)n_total);                    // perm staging
+    s += 2 * align_up(sizeof(double) * GAP_PARTS) + 2 * align_up(sizeof(double) * WSQ_PARTS);
+    s += align_up(sizeof(double) * 4);
+    s += align_up(sizeof(int));
+    return s;
+}
+
+size_t chunk_bytes(bool dense, int64_t n_rows, int64_t entries)
+{
+    size_t s = 0;
+    if (!dense) {
+        s += align_up(sizeof(int32_t) * (size_t)(n_rows + 1));
+        s += align_up(sizeof(int32_t) * (size_t)entries);
+    }
+    s += align_up(sizeof(float) * (size_t)entries);
+    s += 3 * align_up(sizeof(float) * (size_t)n_rows);
+    return s;
+}
+
+void seg_begin(chicle_ctx *c, int s)
+{
+    if (c->profiling) (void)hipEventRecord(c->seg[s].start, c->stream);
+}
+void seg_end(chicle_ctx *c, int s)
+{
+    if (c->profiling) {
+        (void)hipEventRecord(c->seg[s].stop, c->stream);
+        c->seg[s].recorded = true;
+    }
+}
+
+int check_deferred(chicle_ctx *c)
+{
+    int flag = 0;
+    HIP_TRY(c, hipMemcpyAsync(&flag, c->err_dev, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (flag) {
+        HIP_TRY(c, hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream));
+        if (flag & ERR_PERM_RANGE)
+            return fail(c, CHICLE_EDEVICE, "a visiting-order entry was outside [0, rows of its solver)");
+        return fail(c, CHICLE_EDEVICE, "kernel error flag %d", flag);
+    }
+    return CHICLE_OK;
+}
+
+int grid_for(int64_t items, int per_block, int cap)
+{
+    int64_t g = (items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+int seed_all(chicle_ctx *c)
+{
+    if (c->K <= 0) return CHICLE_OK;
+    const int g = grid_for(c->d, 256, 2048);
+    hipLaunchKernelGGL(seed_private, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v,
+                       (int64_t)c->d, c->K);
+    HIP_TRY(c, hipGetLastError());
+    return CHICLE_OK;
+}
+
+RoundScalars scalars(const chicle_ctx *c)
+{
+    RoundScalars s;
+    const double cc = c->lambda * (double)c->n_total / (double)c->K;
+    s.c = (float)cc;
+    s.inv_c = (float)(1.0 / cc);
+    s.inv_sigma = (float)(1.0 / (double)c->K);
+    s.K = c->K;
+    return s;
+}
+
+template <int LOSS>
+int launch_rowwise(chicle_ctx *c, const int32_t *perm)
+{
+    const RoundScalars sc = scalars(c);
+    const size_t list_bytes = 2 * sizeof(int) * (size_t)std::max(c->max_list, 1);
+    if (c->dense) {
+        const bool v_lds = c->d <= DENSE_V_LDS_MAX_D;
+        const size_t sh = list_bytes + (v_lds ? sizeof(float) * (size_t)c->d : 0);
+        if (v_lds)
+            hipLaunchKernelGGL((sdca_rowwise_dense<LOSS, 64, true>), dim3(c->K), dim3(64), sh, c->stream,
+                               c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
+                               perm, c->v, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
+        else
+            hipLaunchKernelGGL((sdca_rowwise_dense<LOSS, 256, false>), dim3(c->K), dim3(256), sh, c->stream,
+                               c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
+                               perm, c->v, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
+    } else {
+        const double avg = c->n_total ? (double)c->total_entries / (double)c->n_total : 0.0;
+        if (avg <= 96.0)
+            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64>), dim3(c->K), dim3(64), list_bytes, c->stream,
+                               c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
+                               perm, c->v, c->ld_v, sc, c->err_dev);
+        else
+            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 256>), dim3(c->K), dim3(256), list_bytes, c->stream,
+                               c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
+                               perm, c->v, c->ld_v, sc, c->err_dev);
+    }
+    HIP_TRY(c, hipGetLastError());
+    return CHICLE_OK;
+}
+
+template <int LOSS, int LPR>
+void launch_gap_rows(chicle_ctx *c, int grid)
+{
+    if (c->dense)
+        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPR>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+                           c->item_prefix_dev, c->n_chunks, c->gap_items, (int)c->d, c->w, c->part_loss,
+                           c->part_conj);
+    else
+        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPR>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+                           c->item_prefix_dev, c->n_chunks, c->gap_items, c->w, c->part_loss, c->part_conj);
+}
+
+template <int LOSS>
+void launch_gap_lpr(chicle_ctx *c, int grid)
+{
+    switch (c->gap_lpr) {
+        case 4: launch_gap_rows<LOSS, 4>(c, grid); break;
+        case 8: launch_gap_rows<LOSS, 8>(c, grid); break;
+        case 16: launch_gap_rows<LOSS, 16>(c, grid); break;
+        case 32: launch_gap_rows<LOSS, 32>(c, grid); break;
+        default: launch_gap_rows<LOSS, 64>(c, grid); break;
+    }
+}
+
+int choose_lpr(double avg_row_len)
+{
+    if (avg_row_len <= 6) return 4;
+    if (avg_row_len <= 12) return 8;
+    if (avg_row_len <= 24) return 16;
+    if (avg_row_len <= 48) return 32;
+    return 64;
+}
+
+// Greedy table shared by chicle_balance; integers only.
+bool greedy_table(const int64_t *load, int32_t n_chunks, int32_t K, const int32_t *speed, int32_t *out)
+{
+    std::vector<int32_t> order(n_chunks);
+    for (int32_t i = 0; i < n_chunks; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return load[a] > load[b]; });
+    std::vector<int64_t> L(K, 0);
+    for (int32_t c : order) {
+        int32_t best = 0;
+        for (int32_t k = 1; k < K; ++k) {
+            const __int128 fk = (__int128)(L[k] + load[c]) * (speed ? speed[best] : 1);
+            const __int128 fb = (__int128)(L[best] + load[c]) * (speed ? speed[k] : 1);
+            if (fk < fb) best = k;
+        }
+        out[c] = best;
+        L[best] += load[c];
+    }
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int32_t n_chunks,
+                          int32_t max_solvers, int32_t dense)
+{
+    if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
+    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers);
+    // chunk blocks: exact array bytes plus alignment slack per array and chunk
+    const size_t per_chunk_slack = 6 * ALIGN;
+    if (dense)
+        s += sizeof(float) * (size_t)total_entries + 3 * sizeof(float) * (size_t)n_total;
+    else
+        s += (sizeof(int32_t) + sizeof(float)) * (size_t)total_entries +
+             sizeof(int32_t) * ((size_t)n_total + (size_t)n_chunks) + 3 * sizeof(float) * (size_t)n_total;
+    s += per_chunk_slack * (size_t)n_chunks;
+    return s + ALIGN;
+}
+
+int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, double lambda,
+                  int32_t n_chunks, int32_t max_solvers, int32_t dense, int64_t total_entries,
+                  void *device_arena, size_t arena_bytes, void *hip_stream)
+{
+    if (!out) return CHICLE_EINVAL;
+    *out = nullptr;
+    if ((loss != CHICLE_LOSS_HINGE && loss != CHICLE_LOSS_SQUARED) || n_total <= 0 ||
+        n_total > INT32_MAX || d <= 0 || !(lambda > 0.0) || n_chunks <= 0 || max_solvers <= 0 ||
+        total_entries < 0 || !device_arena || ((uintptr_t)device_arena % ALIGN) != 0)
+        return CHICLE_EINVAL;
+    const size_t need = chicle_arena_bytes(n_total, total_entries, d, n_chunks, max_solvers, dense);
+    if (arena_bytes < need) return CHICLE_ENOMEM;
+    chicle_ctx *c = new (std::nothrow) chicle_ctx();
+    if (!c) return CHICLE_ENOMEM;
+    c->loss = loss; c->n_total = n_total; c->d = d; c->ld_v = pad_d(d); c->lambda = lambda;
+    c->n_chunks = n_chunks; c->max_solvers = max_solvers; c->dense = dense != 0;
+    c->total_entries = total_entries;
+    c->arena = (char *)device_arena; c->arena_bytes = arena_bytes;
+    c->stream = (hipStream_t)hip_stream;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CHICLE_EDEVICE; }
+
+    c->chunks_dev = (ChunkDev *)carve(c, sizeof(ChunkDev) * (size_t)n_chunks);
+    c->solvers_dev = (SolverDev *)carve(c, sizeof(SolverDev) * (size_t)max_solvers);
+    c->solver_chunks_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
+    c->solver_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
+    c->item_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * ((size_t)n_chunks + 1));
+    c->w = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
+    c->dw_tmp = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
+    c->v = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
+    c->perm_stage = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
+    c->part_loss = (double *)carve(c, sizeof(double) * GAP_PARTS);
+    c->part_conj = (double *)carve(c, sizeof(double) * GAP_PARTS);
+    c->part_wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
+    c->part_unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
+    c->gap_out = (double *)carve(c, sizeof(double) * 4);
+    c->err_dev = (int *)carve(c, sizeof(int));
+    if (!c->err_dev) { delete c; return CHICLE_ENOMEM; }
+
+    c->chunks.assign(n_chunks, ChunkDev{});
+    c->loaded.assign(n_chunks, 0);
+    bool ok = hipMemsetAsync(c->w, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->dw_tmp, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->v, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess;
+    for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
+        ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
+    if (!ok) { chicle_destroy(c); return CHICLE_EDEVICE; }
+    *out = c;
+    return CHICLE_OK;
+}
+
+static int load_common(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, int64_t entries)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state != ST_LOADING) return fail(c, CHICLE_ESTATE, "chunks can only be loaded before the first assign");
+    if (chunk_id < 0 || chunk_id >= c->n_chunks) return fail(c, CHICLE_EINVAL, "chunk id %d out of range", chunk_id);
+    if (c->loaded[chunk_id]) return fail(c, CHICLE_EINVAL, "chunk %d already loaded", chunk_id);
+    if (n_rows <= 0) return fail(c, CHICLE_EINVAL, "chunk %d: n_rows must be positive", chunk_id);
+    if (c->rows_loaded + n_rows > c->n_total) return fail(c, CHICLE_EINVAL, "more rows than n_total");
+    if (c->entries_loaded + entries > c->total_entries)
+        return fail(c, CHICLE_EINVAL, "more stored entries than total_entries");
+    if (c->used + chunk_bytes(c->dense, n_rows, entries) > c->arena_bytes)
+        return fail(c, CHICLE_ENOMEM, "chunk store full");
+    return CHICLE_OK;
+}
+
+static int check_state_arrays(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const float *y,
+                              const float *alpha0)
+{
+    if (!y) return fail(c, CHICLE_EINVAL, "chunk %d: y is NULL", chunk_id);
+    for (int32_t r = 0; r < n_rows; ++r) {
+        if (!std::isfinite(y[r])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: label not finite", chunk_id, r);
+        if (c->loss == CHICLE_LOSS_HINGE && y[r] != 1.0f && y[r] != -1.0f)
+            return fail(c, CHICLE_EINVAL, "chunk %d row %d: hinge label must be +1 or -1", chunk_id, r);
+        if (alpha0) {
+            if (!std::isfinite(alpha0[r])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: alpha not finite", chunk_id, r);
+            if (c->loss == CHICLE_LOSS_HINGE && (alpha0[r] < 0.0f || alpha0[r] > 1.0f))
+                return fail(c, CHICLE_EINVAL, "chunk %d row %d: hinge alpha outside [0,1]", chunk_id, r);
+        }
+    }
+    return CHICLE_OK;
+}
+
+static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const float *y, const float *alpha0,
+                       const std::vector<float> &q)
+{
+    const int32_t n_rows = ch.n_rows;
+    float *yd = (float *)carve(c, sizeof(float) * (size_t)n_rows);
+    float *ad = (float *)carve(c, sizeof(float) * (size_t)n_rows);
+    float *qd = (float *)carve(c, sizeof(float) * (size_t)n_rows);
+    if (!qd) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    ch.y = yd; ch.alpha = ad; ch.q = qd;
+    HIP_TRY(c, hipMemcpyAsync(yd, y, sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
+    if (alpha0)
+        HIP_TRY(c, hipMemcpyAsync(ad, alpha0, sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
+    else
+        HIP_TRY(c, hipMemsetAsync(ad, 0, sizeof(float) * (size_t)n_rows, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(qd, q.data(), sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));   // host arrays are the caller's again on return
+    c->chunks[chunk_id] = ch;
+    c->loaded[chunk_id] = 1;
+    c->n_loaded += 1;
+    c->rows_loaded += n_rows;
+    c->entries_loaded += ch.nnz;
+    return CHICLE_OK;
+}
+
+int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
+                          const int32_t *col, const float *val, const float *y, const float *alpha0)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->dense) return fail(c, CHICLE_EINVAL, "context holds dense chunks");
+    if (!row_ptr || n_rows <= 0) return fail(c, CHICLE_EINVAL, "chunk %d: row_ptr NULL or no rows", chunk_id);
+    if (row_ptr[0] != 0) return fail(c, CHICLE_EINVAL, "chunk %d: row_ptr[0] must be 0", chunk_id);
+    for (int32_t r = 0; r < n_rows; ++r)
+        if (row_ptr[r + 1] < row_ptr[r]) return fail(c, CHICLE_EINVAL, "chunk %d: row_ptr decreases at row %d", chunk_id, r);
+    const int64_t nnz = row_ptr[n_rows];
+    int rc = load_common(c, chunk_id, n_rows, nnz);
+    if (rc) return rc;
+    if (nnz > 0 && (!col || !val)) return fail(c, CHICLE_EINVAL, "chunk %d: col/val NULL", chunk_id);
+    rc = check_state_arrays(c, chunk_id, n_rows, y, alpha0);
+    if (rc) return rc;
+    std::vector<float> q(n_rows);
+    for (int32_t r = 0; r < n_rows; ++r) {
+        double s = 0.0;
+        for (int32_t p = row_ptr[r]; p < row_ptr[r + 1]; ++p) {
+            if (col[p] < 0 || col[p] >= c->d) return fail(c, CHICLE_EINVAL, "chunk %d row %d: column %d outside [0,d)", chunk_id, r, col[p]);
+            if (p > row_ptr[r] && col[p] <= col[p - 1]) return fail(c, CHICLE_EINVAL, "chunk %d row %d: columns not strictly ascending", chunk_id, r);
+            if (!std::isfinite(val[p])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: value not finite", chunk_id, r);
+            s += (double)val[p] * (double)val[p];
+        }
+        q[r] = (float)s;
+    }
+    ChunkDev ch{};
+    ch.n_rows = n_rows; ch.nnz = nnz;
+    int32_t *rp = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(n_rows + 1));
+    int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1));
+    float *vd = (float *)carve(c, sizeof(float) * (size_t)std::max<int64_t>(nnz, 1));
+    if (!vd) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    ch.row_ptr = rp; ch.col = cd; ch.val = vd;
+    HIP_TRY(c, hipMemcpyAsync(rp, row_ptr, sizeof(int32_t) * (size_t)(n_rows + 1), hipMemcpyHostToDevice, c->stream));
+    if (nnz > 0) {
+        HIP_TRY(c, hipMemcpyAsync(cd, col, sizeof(int32_t) * (size_t)nnz, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(vd, val, sizeof(float) * (size_t)nnz, hipMemcpyHostToDevice, c->stream));
+    }
+    return finish_load(c, chunk_id, ch, y, alpha0, q);
+}
+
+int chicle_load_chunk_dense(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const float *X,
+                            const float *y, const float *alpha0)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (!c->dense) return fail(c, CHICLE_EINVAL, "context holds CSR chunks");
+    if (!X || n_rows <= 0) return fail(c, CHICLE_EINVAL, "chunk %d: X NULL or no rows", chunk_id);
+    const int64_t entries = (int64_t)n_rows * c->d;
+    int rc = load_common(c, chunk_id, n_rows, entries);
+    if (rc) return rc;
+    rc = check_state_arrays(c, chunk_id, n_rows, y, alpha0);
+    if (rc) return rc;
+    std::vector<float> q(n_rows);
+    for (int32_t r = 0; r < n_rows; ++r) {
+        double s = 0.0;
+        const float *x = X + (int64_t)r * c->d;
+        for (int32_t j = 0; j < c->d; ++j) {
+            if (!std::isfinite(x[j])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: value not finite", chunk_id, r);
+            s += (double)x[j] * (double)x[j];
+        }
+        q[r] = (float)s;
+    }
+    ChunkDev ch{};
+    ch.n_rows = n_rows; ch.nnz = entries;
+    float *xd = (float *)carve(c, sizeof(float) * (size_t)entries);
+    if (!xd) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    ch.val = xd;
+    HIP_TRY(c, hipMemcpyAsync(xd, X, sizeof(float) * (size_t)entries, hipMemcpyHostToDevice, c->stream));
+    return finish_load(c, chunk_id, ch, y, alpha0, q);
+}
+
+int chicle_balance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const int32_t *speed_q,
+                   int32_t *chunk_to_solver_out)
+{
+    if (!chunk_load || !chunk_to_solver_out || n_chunks < 0 || K <= 0) return CHICLE_EINVAL;
+    for (int32_t i = 0; i < n_chunks; ++i)
+        if (chunk_load[i] < 0) return CHICLE_EINVAL;
+    if (speed_q)
+        for (int32_t k = 0; k < K; ++k)
+            if (speed_q[k] <= 0) return CHICLE_EINVAL;
+    greedy_table(chunk_load, n_chunks, K, speed_q, chunk_to_solver_out);
+    return CHICLE_OK;
+}
+
+int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state == ST_EPOCH_DONE)
+        return fail(c, CHICLE_ESTATE, "solvers own the chunks until their updates are aggregated");
+    if (K <= 0 || K > c->max_solvers) return fail(c, CHICLE_EINVAL, "K=%d outside [1, max_solvers=%d]", K, c->max_solvers);
+    if (!chunk_to_solver) return fail(c, CHICLE_EINVAL, "table is NULL");
+    if (c->n_loaded != c->n_chunks) return fail(c, CHICLE_EINVAL, "%d of %d chunks loaded", c->n_loaded, c->n_chunks);
+    if (c->rows_loaded != c->n_total) return fail(c, CHICLE_EINVAL, "chunks hold %lld rows, n_total is %lld", (long long)c->rows_loaded, (long long)c->n_total);
+    std::vector<int32_t> count(K, 0);
+    for (int32_t i = 0; i < c->n_chunks; ++i) {
+        if (chunk_to_solver[i] < 0 || chunk_to_solver[i] >= K)
+            return fail(c, CHICLE_EINVAL, "chunk %d assigned to solver %d, K=%d", i, chunk_to_solver[i], K);
+        count[chunk_to_solver[i]] += 1;
+    }
+    int max_list = 0;
+    for (int32_t k = 0; k < K; ++k) max_list = std::max(max_list, count[k]);
+    if (max_list > MAX_LIST_LDS) return fail(c, CHICLE_EINVAL, "a solver owns %d chunks, limit %d", max_list, MAX_LIST_LDS);
+
+    std::vector<SolverDev> sol(K);
+    std::vector<int32_t> list(c->n_chunks), prefix(c->n_chunks);
+    int32_t pos = 0;
+    int64_t perm_off = 0;
+    for (int32_t k = 0; k < K; ++k) {
+        sol[k].list_begin = pos; sol[k].n_chunks = count[k]; sol[k].perm_off = perm_off; sol[k].pad_ = 0;
+        int32_t rows = 0;
+        for (int32_t i = 0; i < c->n_chunks; ++i) {        // ascending chunk id
+            if (chunk_to_solver[i] != k) continue;
+            list[pos] = i; prefix[pos] = rows; rows += c->chunks[i].n_rows; ++pos;
+        }
+        sol[k].n_rows = rows;
+        perm_off += rows;
+    }
+    // work items of the gap kernels: blocks of 256/LPR rows inside a chunk
+    const double avg = c->dense ? (double)c->d : (double)c->total_entries / (double)c->n_total;
+    c->gap_lpr = choose_lpr(avg);
+    const int rows_per_item = 256 / c->gap_lpr;
+    std::vector<int32_t> items(c->n_chunks + 1, 0);
+    for (int32_t i = 0; i < c->n_chunks; ++i)
+        items[i + 1] = items[i] + (c->chunks[i].n_rows + rows_per_item - 1) / rows_per_item;
+
+    // Stream order keeps earlier kernels ahead of these copies; the host vectors are pageable, so the
+    // copies have consumed them when the calls return, but wait anyway before they go out of scope.
+    HIP_TRY(c, hipMemcpyAsync(c->chunks_dev, c->chunks.data(), sizeof(ChunkDev) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->solvers_dev, sol.data(), sizeof(SolverDev) * (size_t)K, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->solver_chunks_dev, list.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->solver_prefix_dev, prefix.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->item_prefix_dev, items.data(), sizeof(int32_t) * ((size_t)c->n_chunks + 1), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->K = K;
+    c->chunk_to_solver.assign(chunk_to_solver, chunk_to_solver + c->n_chunks);
+    c->solvers = sol;
+    c->max_list = max_list;
+    c->gap_items = items[c->n_chunks];
+    c->state = ST_READY;
+    return seed_all(c);
+}
+
+int chicle_solver_rows(chicle_ctx *c, int64_t *rows_out)
+{
+    if (!c || !rows_out) return CHICLE_EINVAL;
+    if (c->state == ST_LOADING) return fail(c, CHICLE_ESTATE, "no assignment yet");
+    for (int32_t k = 0; k < c->K; ++k) rows_out[k] = c->solvers[k].n_rows;
+    return CHICLE_OK;
+}
+
+int chicle_set_solver(chicle_ctx *c, int32_t kind)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE)
+        return fail(c, CHICLE_EINVAL, "solver kind %d not available", kind);
+    c->solver_kind = kind;
+    return CHICLE_OK;
+}
+
+int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
+    if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
+    seg_begin(c, CHICLE_SEG_LOCAL_EPOCH);
+    seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+    const int rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device) : launch_rowwise<1>(c, perm_device);
+    seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    seg_end(c, CHICLE_SEG_LOCAL_EPOCH);
+    if (rc) return rc;
+    c->state = ST_EPOCH_DONE;
+    return CHICLE_OK;
+}
+
+int chicle_local_epoch_host_perm(chicle_ctx *c, const int32_t *perm_host)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
+    if (!perm_host) return fail(c, CHICLE_EINVAL, "perm is NULL");
+    HIP_TRY(c, hipMemcpyAsync(c->perm_stage, perm_host, sizeof(int32_t) * (size_t)c->n_total, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return chicle_local_epoch(c, c->perm_stage);
+}
+
+int chicle_aggregate(chicle_ctx *c)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "no local epoch pending");
+    seg_begin(c, CHICLE_SEG_AGGREGATE);
+    const int64_t d4 = c->ld_v / 4;
+    const int g = grid_for(d4, 256, 4096);
+    hipLaunchKernelGGL(aggregate_broadcast, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v, d4,
+                       c->K, (float)(1.0 / (double)c->K));
+    seg_end(c, CHICLE_SEG_AGGREGATE);
+    HIP_TRY(c, hipGetLastError());
+    c->state = ST_READY;
+    return CHICLE_OK;
+}
+
+int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, "gap is defined on the aggregated state");
+    seg_begin(c, CHICLE_SEG_GAP);
+    const int grid = std::max(1, std::min(c->gap_items, GAP_PARTS));
+    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, grid); else launch_gap_lpr<1>(c, grid);
+    const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
+    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w, (int64_t)c->d, c->part_wsq, c->part_unused);
+    hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, c->part_loss, c->part_conj, grid,
+                       c->part_wsq, gw, c->gap_out);
+    seg_end(c, CHICLE_SEG_GAP);
+    HIP_TRY(c, hipGetLastError());
+    double h[3];
+    HIP_TRY(c, hipMemcpyAsync(h, c->gap_out, sizeof h, hipMemcpyDeviceToHost, c->stream));
+    const int rc = check_deferred(c);   // synchronises
+    if (rc) return rc;
+    const double n = (double)c->n_total;
+    const double P = 0.5 * c->lambda * h[2] + h[0] / n;
+    const double D = -0.5 * c->lambda * h[2] - h[1] / n;
+    if (primal) *primal = P;
+    if (dual) *dual = D;
+    if (gap) *gap = P - D;
+    return CHICLE_OK;
+}
+
+int chicle_get_w(chicle_ctx *c, float *w_out)
+{
+    if (!c || !w_out) return CHICLE_EINVAL;
+    HIP_TRY(c, hipMemcpyAsync(w_out, c->w, sizeof(float) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
+    return check_deferred(c);
+}
+
+int chicle_set_w(chicle_ctx *c, const float *w_in)
+{
+    if (!c || !w_in) return CHICLE_EINVAL;
+    if (c->state == ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "aggregate first");
+    HIP_TRY(c, hipMemcpyAsync(c->w, w_in, sizeof(float) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return c->state == ST_READY ? seed_all(c) : CHICLE_OK;
+}
+
+int chicle_get_delta_w(chicle_ctx *c, int32_t solver, float *dw_out)
+{
+    if (!c || !dw_out) return CHICLE_EINVAL;
+    if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "updates exist only between local_epoch and aggregate");
+    if (solver < -1 || solver >= c->K) return fail(c, CHICLE_EINVAL, "solver %d, K=%d", solver, c->K);
+    const int g = grid_for(c->d, 256, 4096);
+    hipLaunchKernelGGL(delta_w_out, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v, (int64_t)c->d,
+                       c->K, solver, (float)(1.0 / (double)c->K), c->dw_tmp);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(dw_out, c->dw_tmp, sizeof(float) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
+    return check_deferred(c);
+}
+
+int chicle_get_alpha(chicle_ctx *c, int32_t chunk_id, float *alpha_out)
+{
+    if (!c || !alpha_out) return CHICLE_EINVAL;
+    if (chunk_id < 0 || chunk_id >= c->n_chunks || !c->loaded[chunk_id]) return fail(c, CHICLE_EINVAL, "chunk %d not loaded", chunk_id);
+    const ChunkDev &ch = c->chunks[chunk_id];
+    HIP_TRY(c, hipMemcpyAsync(alpha_out, ch.alpha, sizeof(float) * (size_t)ch.n_rows, hipMemcpyDeviceToHost, c->stream));
+    return check_deferred(c);
+}
+
+int chicle_set_alpha(chicle_ctx *c, int32_t chunk_id, const float *alpha_in)
+{
+    if (!c || !alpha_in) return CHICLE_EINVAL;
+    if (c->state == ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "solvers own the chunks until their updates are aggregated");
+    if (chunk_id < 0 || chunk_id >= c->n_chunks || !c->loaded[chunk_id]) return fail(c, CHICLE_EINVAL, "chunk %d not loaded", chunk_id);
+    const ChunkDev &ch = c->chunks[chunk_id];
+    for (int32_t r = 0; r < ch.n_rows; ++r) {
+        if (!std::isfinite(alpha_in[r])) return fail(c, CHICLE_EINVAL, "alpha not finite at row %d", r);
+        if (c->loss == CHICLE_LOSS_HINGE && (alpha_in[r] < 0.f || alpha_in[r] > 1.f))
+            return fail(c, CHICLE_EINVAL, "hinge alpha outside [0,1] at row %d", r);
+    }
+    HIP_TRY(c, hipMemcpyAsync(ch.alpha, alpha_in, sizeof(float) * (size_t)ch.n_rows, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return CHICLE_OK;
+}
+
+int chicle_get_assignment(chicle_ctx *c, int32_t *chunk_to_solver_out, int32_t *K_out)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (c->state == ST_LOADING) return fail(c, CHICLE_ESTATE, "no assignment yet");
+    if (chunk_to_solver_out) std::memcpy(chunk_to_solver_out, c->chunk_to_solver.data(), sizeof(int32_t) * (size_t)c->n_chunks);
+    if (K_out) *K_out = c->K;
+    return CHICLE_OK;
+}
+
+int chicle_w_device(chicle_ctx *c, const float **w_device_out)
+{
+    if (!c || !w_device_out) return CHICLE_EINVAL;
+    *w_device_out = c->w;
+    return CHICLE_OK;
+}
+
+int chicle_sync(chicle_ctx *c)
+{
+    if (!c) return CHICLE_EINVAL;
+    return check_deferred(c);
+}
+
+int chicle_set_profiling(chicle_ctx *c, int32_t on)
+{
+    if (!c) return CHICLE_EINVAL;
+    c->profiling = on != 0;
+    return CHICLE_OK;
+}
+
+int chicle_last_kernel_ms(chicle_ctx *c, int32_t segment, float *ms_out)
+{
+    if (!c || !ms_out || segment < 0 || segment >= CHICLE_SEG_COUNT) return CHICLE_EINVAL;
+    if (!c->seg[segment].recorded) return fail(c, CHICLE_ESTATE, "segment %d was not recorded (profiling off, or not run)", segment);
+    HIP_TRY(c, hipEventSynchronize(c->seg[segment].stop));
+    HIP_TRY(c, hipEventElapsedTime(ms_out, c->seg[segment].start, c->seg[segment].stop));
+    return CHICLE_OK;
+}
+
+const char *chicle_last_error(chicle_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+void chicle_destroy(chicle_ctx *c)
+{
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (int s = 0; s < CHICLE_SEG_COUNT; ++s) {
+        if (c->seg[s].start) (void)hipEventDestroy(c->seg[s].start);
+        if (c->seg[s].stop) (void)hipEventDestroy(c->seg[s].stop);
+    }
+    delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,40 @@
+// Plain structs shared by host code and kernels of the CoCoA-round library.
+#pragma once
+#include <stdint.h>
+
+namespace chicle {
+
+// One data chunk as the kernels see it (paper Section 4.4: sparse or dense rows plus per-sample
+// state in one contiguous block; all pointers point into that block).
+struct ChunkDev {
+    const int32_t *row_ptr;   // CSR: n_rows + 1 chunk-local offsets; dense: nullptr
+    const int32_t *col;       // CSR column ids; dense: nullptr
+    const float *val;         // CSR values, or dense row-major n_rows x d
+    const float *y;           // labels / targets
+    float *alpha;             // dual variables (the per-sample state)
+    const float *q;           // squared row norms
+    int32_t n_rows;
+    int32_t pad_;
+    int64_t nnz;              // stored entries
+};
+
+// One local solver under the current assignment.
+struct SolverDev {
+    int64_t perm_off;         // where this solver's visiting order starts in the concatenated array
+    int32_t list_begin;       // first entry of this solver in solver_chunks[] / solver_prefix[]
+    int32_t n_chunks;
+    int32_t n_rows;
+    int32_t pad_;
+};
+
+// Scalars of one round.
+struct RoundScalars {
+    float c;        // lambda n / sigma
+    float inv_c;    // sigma / (lambda n)
+    float inv_sigma;
+    int32_t K;
+};
+
+constexpr int ERR_PERM_RANGE = 1;
+
+}  // namespace chicle

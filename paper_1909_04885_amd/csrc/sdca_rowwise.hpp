@@ -1,0 +1,165 @@
+// Local solver, one coordinate step at a time (paper Section 2.2: L = 1, H = all local samples).
+//
+// One workgroup per solver.  Every step is: row dot product against the solver's private vector
+// (workgroup reduction), closed-form dual step, alpha update inside the chunk, scatter of the row
+// into the private vector.  The private vector is v_k = w + sigma * Delta w_k, which turns the CoCoA
+// subproblem step into a plain coordinate step against v_k:
+//     hinge   : a' = clip(a + c (1 - y z) / q, 0, 1),  c = lambda n / sigma
+//     squared : delta = (y - z - a) / (1 + q / c)
+//     v_k += (delta s / c) x_i,  s = y (hinge) or 1 (squared).
+#pragma once
+#include <hip/hip_runtime.h>
+#include "device_types.hpp"
+
+namespace chicle {
+
+template <int LOSS>
+__device__ __forceinline__ float dual_step(float a, float y, float z, float q, float c)
+{
+    if (LOSS == 0) {
+        float an = a + c * (1.0f - y * z) / q;
+        an = fminf(fmaxf(an, 0.0f), 1.0f);
+        return an - a;
+    }
+    return (y - z - a) / (1.0f + q / c);
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// Sum over the workgroup; every thread gets the result.  red: BLOCK/64 floats of LDS.
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float x, float *red)
+{
+    x = wave_sum(x);
+    if (BLOCK == 64) return x;
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();                       // red may still be read from the previous use
+    if ((threadIdx.x & 63) == 0) red[wave] = x;
+    __syncthreads();
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < BLOCK / 64; ++i) s += red[i];
+    return s;
+}
+
+// Largest j in [0, n) with prefix[j] <= lr (prefix ascending, prefix[0] = 0).
+__device__ __forceinline__ int find_chunk(const int *prefix, int n, int lr)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (prefix[mid] <= lr) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Sparse rows.  Dynamic LDS: 2 * max_list ints (chunk ids, then local-row prefixes).
+template <int LOSS, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
+    const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
+    const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
+    const int32_t *__restrict__ perm, float *v_all, int64_t ld_v, RoundScalars sc, int *err)
+{
+    extern __shared__ int lists[];
+    __shared__ float red[BLOCK / 64];
+    const SolverDev S = solvers[blockIdx.x];
+    int *l_chunk = lists;
+    int *l_prefix = lists + S.n_chunks;
+    for (int i = threadIdx.x; i < S.n_chunks; i += BLOCK) {
+        l_chunk[i] = solver_chunks[S.list_begin + i];
+        l_prefix[i] = solver_prefix[S.list_begin + i];
+    }
+    __syncthreads();
+    float *v = v_all + (int64_t)blockIdx.x * ld_v;
+    const int32_t *pk = perm + S.perm_off;
+    const int tid = threadIdx.x;
+
+    for (int t = 0; t < S.n_rows; ++t) {
+        const int lr = pk[t];
+        if ((unsigned)lr >= (unsigned)S.n_rows) {
+            if (tid == 0) atomicOr(err, ERR_PERM_RANGE);
+            continue;
+        }
+        const int j = find_chunk(l_prefix, S.n_chunks, lr);
+        const ChunkDev &ch = chunks[l_chunk[j]];
+        const int r = lr - l_prefix[j];
+        const float q = ch.q[r];
+        if (q == 0.0f) continue;
+        const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
+        const float y = ch.y[r];
+        const float a = ch.alpha[r];
+        const int32_t *col = ch.col;
+        const float *val = ch.val;
+        float part = 0.0f;
+        for (int p = b + tid; p < e; p += BLOCK) part += val[p] * v[col[p]];
+        const float z = block_sum<BLOCK>(part, red);
+        const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
+        if (tid == 0) ch.alpha[r] = a + delta;
+        const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
+        if (coef != 0.0f)
+            for (int p = b + tid; p < e; p += BLOCK) v[col[p]] += coef * val[p];
+        __syncthreads();   // the next step's gather must see this scatter
+    }
+}
+
+// Dense rows.  The private vector is staged in LDS when it fits (V_LDS), else it stays in HBM.
+// Dynamic LDS: 2 * max_list ints, then d floats when V_LDS.
+template <int LOSS, int BLOCK, bool V_LDS>
+__global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
+    const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
+    const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
+    const int32_t *__restrict__ perm, float *v_all, int64_t ld_v, int d, int max_list,
+    RoundScalars sc, int *err)
+{
+    extern __shared__ int lists[];
+    __shared__ float red[BLOCK / 64];
+    const SolverDev S = solvers[blockIdx.x];
+    int *l_chunk = lists;
+    int *l_prefix = lists + max_list;
+    float *v_lds = reinterpret_cast<float *>(lists + 2 * max_list);
+    float *v_glb = v_all + (int64_t)blockIdx.x * ld_v;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < S.n_chunks; i += BLOCK) {
+        l_chunk[i] = solver_chunks[S.list_begin + i];
+        l_prefix[i] = solver_prefix[S.list_begin + i];
+    }
+    if (V_LDS)
+        for (int i = tid; i < d; i += BLOCK) v_lds[i] = v_glb[i];
+    __syncthreads();
+    float *v = V_LDS ? v_lds : v_glb;
+    const int32_t *pk = perm + S.perm_off;
+
+    for (int t = 0; t < S.n_rows; ++t) {
+        const int lr = pk[t];
+        if ((unsigned)lr >= (unsigned)S.n_rows) {
+            if (tid == 0) atomicOr(err, ERR_PERM_RANGE);
+            continue;
+        }
+        const int j = find_chunk(l_prefix, S.n_chunks, lr);
+        const ChunkDev &ch = chunks[l_chunk[j]];
+        const int r = lr - l_prefix[j];
+        const float q = ch.q[r];
+        if (q == 0.0f) continue;
+        const float *x = ch.val + (int64_t)r * d;
+        const float y = ch.y[r];
+        const float a = ch.alpha[r];
+        float part = 0.0f;
+        for (int p = tid; p < d; p += BLOCK) part += x[p] * v[p];
+        const float z = block_sum<BLOCK>(part, red);
+        const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
+        if (tid == 0) ch.alpha[r] = a + delta;
+        const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
+        if (coef != 0.0f)
+            for (int p = tid; p < d; p += BLOCK) v[p] += coef * x[p];
+        __syncthreads();
+    }
+    if (V_LDS)
+        for (int i = tid; i < d; i += BLOCK) v_glb[i] = v_lds[i];
+}
+
+}  // namespace chicle

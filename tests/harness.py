@@ -1,0 +1,93 @@
+"""Lock-step driver used by the GPU parity tests: the HIP library and the CPU oracle run the same
+rounds on the same seeded inputs and the same visiting orders, compared after every step."""
+from __future__ import annotations
+
+import functools
+
+import numpy as np
+
+from workloads import get_config, make_problem, round_permutations
+from workloads.configs import k_for_round, speeds_for
+
+# Tolerances of the target: per-round relative L2 error of every Delta w, relative error of the final
+# duality gap.  fp32 kernels against the fp64 oracle, free-running (no resynchronisation).
+TOL_DW = 1e-4
+TOL_GAP = 1e-3
+
+
+@functools.lru_cache(maxsize=2)
+def cached_problem(name: str, size: str):
+    cfg = get_config(name, size)
+    return cfg, make_problem(cfg)
+
+
+def rel_l2(got: np.ndarray, ref: np.ndarray, floor: float) -> float:
+    den = max(float(np.linalg.norm(ref)), floor)
+    return float(np.linalg.norm(got.astype(np.float64) - ref)) / den
+
+
+def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sample_solvers=None,
+                 check_alpha_every=0, log=None):
+    """Returns a dict of per-round records; raises AssertionError on the first violation."""
+    o = oracle_mod.OracleCoCoA.from_problem(p)
+    maxK = max(k for _, k in cfg["schedule"])
+    g = binding_mod.ChicleRound.from_problem(p, max_solvers=maxK)
+    g.set_solver(solver)
+    rounds = cfg["rounds"] if rounds is None else rounds
+    K = None
+    rec = []
+    loads = p.chunk_nnz()
+    for r in range(rounds):
+        Kr = k_for_round(cfg, r)
+        if Kr != K:
+            K = Kr
+            sp = speeds_for(cfg, K)
+            t_ref = oracle_mod.assign_greedy(loads, K, sp)
+            t_gpu = binding_mod.balance(loads, K, sp)
+            assert np.array_equal(t_ref, t_gpu), "chunk -> solver table differs at round %d" % r
+            alpha_before = [g.get_alpha(c) for c in range(min(p.n_chunks, 4))] if r > 0 else None
+            o.assign(K, t_ref)
+            g.assign(K, t_gpu)
+            back, kb = g.get_assignment()
+            assert kb == K and np.array_equal(back, t_ref)
+            assert list(g.solver_rows()) == o.rows_per_solver()
+            if alpha_before is not None:      # state stays with its chunk across a reassignment
+                for c, a in enumerate(alpha_before):
+                    assert np.array_equal(a, g.get_alpha(c))
+        perms = round_permutations(cfg["seed"], r, o.rows_per_solver())
+        g.local_epoch(g.upload_perm(perms))
+        wnorm = float(np.linalg.norm(o.w))
+        worst = [0.0]
+        which = set(range(K)) if sample_solvers is None else {s % K for s in sample_solvers}
+
+        def on_delta(k, dw):
+            if k in which:
+                e = rel_l2(g.get_delta_w(k), dw, 1e-12 * max(wnorm, 1.0))
+                worst[0] = max(worst[0], e)
+                assert e <= TOL_DW, "round %d solver %d: Delta w rel L2 error %.3e" % (r, k, e)
+
+        o.local_epoch(perms, keep_deltas=False, on_delta=on_delta)
+        tot = o._pending
+        e_sum = rel_l2(g.get_delta_w(-1), tot, 1e-12 * max(wnorm, 1.0))
+        assert e_sum <= TOL_DW, "round %d: summed Delta w rel L2 error %.3e" % (r, e_sum)
+        o.aggregate()
+        g.aggregate()
+        Pg, Dg, Gg = g.gap()
+        Po, Do, Go, _ = o.gap()
+        e_w = rel_l2(g.get_w(), o.w, 1e-30)
+        rec.append(dict(round=r, K=K, dw_err=worst[0], dw_sum_err=e_sum, w_err=e_w,
+                        gap_gpu=Gg, gap_ref=Go, P_gpu=Pg, P_ref=Po, D_gpu=Dg, D_ref=Do))
+        if log:
+            log("r=%d K=%d dw_err=%.2e sum_err=%.2e w_err=%.2e gap gpu=%.6e ref=%.6e" %
+                (r, K, worst[0], e_sum, e_w, Gg, Go))
+        assert Gg >= -1e-6, "weak duality violated on the GPU side"
+        if check_alpha_every and (r % check_alpha_every == 0 or r == rounds - 1):
+            for c in range(p.n_chunks):
+                r0, r1 = p.chunk_rows(c)
+                a = g.get_alpha(c)
+                assert np.max(np.abs(a.astype(np.float64) - o.alpha[r0:r1])) <= 5e-4, "alpha drift in chunk %d" % c
+    last = rec[-1]
+    assert abs(last["gap_gpu"] - last["gap_ref"]) <= TOL_GAP * abs(last["gap_ref"]), \
+        "final gap %.9e vs %.9e" % (last["gap_gpu"], last["gap_ref"])
+    g.close()
+    return rec

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Mini sizes compare every solver's Delta w each round; full sizes (the sizes the benchmark times)
+compare the summed update every round plus a sample of solvers.  Integer work (the chunk -> solver
+table, rows per solver) must be bit-exact."""
+import sys
+
+import numpy as np
+import pytest
+
+from harness import cached_problem, run_lockstep, TOL_DW, TOL_GAP
+from workloads import get_config, make_problem, round_permutations
+
+pytestmark = pytest.mark.gpu
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def mods(oracle_mod):
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1909_04885_amd as binding
+    return oracle_mod, binding
+
+
+@pytest.mark.parametrize("name", ["dense_hinge", "dense_ridge", "sparse_zipf", "sparse_longrow", "elastic"])
+@pytest.mark.parametrize("solver", ["rowwise"])
+def test_mini_all_solvers_every_round(mods, name, solver):
+    oracle_mod, binding = mods
+    cfg, p = cached_problem(name, "mini")
+    print("\ncase", name, "mini", solver, "n=%d d=%d" % (p.n, p.d), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, solver=solver, check_alpha_every=1, log=_log)
+
+
+@pytest.mark.parametrize("name", ["dense_hinge", "dense_ridge"])
+def test_full_dense(mods, name):
+    oracle_mod, binding = mods
+    cfg, p = cached_problem(name, "full")
+    print("\ncase", name, "full n=%d d=%d" % (p.n, p.d), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, check_alpha_every=10, log=_log)
+
+
+@pytest.mark.parametrize("name", ["sparse_zipf", "elastic"])
+def test_full_sparse_zipf(mods, name):
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "full")
+    cfg = get_config(name, "full")
+    print("\ncase", name, "full n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 3, 7, 31], log=_log)
+
+
+def test_full_sparse_longrow(mods):
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_longrow", "full")
+    print("\ncase sparse_longrow full n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 17, 63], log=_log)
+
+
+# ----------------------------------------------------------------------------- edges and contract
+def _tiny(binding, loss="hinge", dense=False, n=300, d=50, chunk=64, K=3, seed=5):
+    g = np.random.default_rng(seed)
+    X = g.standard_normal((n, d)).astype(np.float32)
+    X[g.random(X.shape) < 0.7] = 0
+    X[3] = 0                       # an empty row
+    y = np.where(g.random(n) < 0.5, 1.0, -1.0).astype(np.float32) if loss == "hinge" else g.standard_normal(n).astype(np.float32)
+    bounds = np.array(list(range(0, n, chunk)) + [n], dtype=np.int64)
+    from workloads.generate import Problem
+    if dense:
+        return Problem("tiny", loss, n, d, 0.01, y, bounds, X=X)
+    mask = X != 0
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(mask.sum(1), out=rp[1:])
+    return Problem("tiny", loss, n, d, 0.01, y, bounds, row_ptr=rp, col=np.nonzero(mask)[1].astype(np.int32), val=X[mask])
+
+
+@pytest.mark.parametrize("loss", ["hinge", "squared"])
+@pytest.mark.parametrize("dense", [False, True])
+def test_tiny_ragged_with_empty_row_and_idle_solver(mods, loss, dense):
+    oracle_mod, binding = mods
+    p = _tiny(binding, loss, dense)
+    o = oracle_mod.OracleCoCoA.from_problem(p)
+    g = binding.ChicleRound.from_problem(p, max_solvers=6)
+    table = np.array([0, 2, 2, 4, 0], dtype=np.int32)          # solvers 1, 3, 5 own nothing
+    o.assign(6, table)
+    g.assign(6, table)
+    P, D, G = g.gap()
+    Po, Do, Go, _ = o.gap()
+    assert abs(G - Go) <= 1e-6 * abs(Go)
+    for r in range(5):
+        perms = round_permutations(9, r, o.rows_per_solver())
+        dws = o.local_epoch(perms)
+        g.local_epoch_host_perm(np.concatenate(perms))
+        for k in range(6):
+            got = g.get_delta_w(k)
+            if o.rows_of[k].size == 0:
+                assert not got.any()
+            else:
+                assert np.linalg.norm(got - dws[k]) <= TOL_DW * np.linalg.norm(dws[k])
+        o.aggregate()
+        g.aggregate()
+        assert abs(g.gap()[2] - o.gap()[2]) <= TOL_GAP * abs(o.gap()[2])
+    r0, r1 = p.chunk_rows(0)
+    assert g.get_alpha(0)[3] == 0.0
+    g.close()
+
+
+def test_ownership_contract_and_errors(mods):
+    oracle_mod, binding = mods
+    p = _tiny(binding)
+    g = binding.ChicleRound(p.loss, p.n, p.d, p.lam, p.n_chunks, 4, False, p.nnz)
+    E = binding.ChicleError
+    rp, col, val, y = p.chunk_csr(0)
+    with pytest.raises(E) as e:
+        g.assign(2, np.zeros(p.n_chunks, dtype=np.int32))       # chunks missing
+    assert e.value.code == -1
+    bad = col.copy(); bad[0] = p.d
+    with pytest.raises(E):
+        g.load_chunk_csr(0, rp, bad, val, y)
+    rp_bad = rp.copy(); rp_bad[2] = rp_bad[1] - 1 if rp_bad[1] > 0 else 0; rp_bad[1] = rp_bad[2] + 1
+    with pytest.raises(E):
+        g.load_chunk_csr(0, rp_bad, col, val, y)
+    with pytest.raises(E):
+        g.load_chunk_csr(0, rp, col, val, y * 0.5)               # hinge label must be +-1
+    g.load_problem(p)
+    with pytest.raises(E):
+        g.load_chunk_csr(0, rp, col, val, y)                      # already loaded
+    with pytest.raises(E):
+        g.assign(5, np.zeros(p.n_chunks, dtype=np.int32))        # K above max_solvers
+    with pytest.raises(E):
+        g.assign(2, np.full(p.n_chunks, 2, dtype=np.int32))      # solver id out of range
+    with pytest.raises(E) as e:
+        g.gap()                                                   # nothing assigned yet
+    assert e.value.code == -3
+    g.assign(2, np.arange(p.n_chunks, dtype=np.int32) % 2)
+    rows = g.solver_rows()
+    perms = round_permutations(0, 0, rows)
+    g.local_epoch_host_perm(np.concatenate(perms))
+    for call in (lambda: g.assign(2, np.zeros(p.n_chunks, dtype=np.int32)),
+                 lambda: g.local_epoch_host_perm(np.concatenate(perms)),
+                 lambda: g.gap(), lambda: g.set_alpha(0, np.zeros(p.chunk_rows(0)[1], dtype=np.float32)),
+                 lambda: g.set_w(np.zeros(p.d, dtype=np.float32))):
+        with pytest.raises(E) as e:
+            call()
+        assert e.value.code == -3
+    g.aggregate()
+    with pytest.raises(E) as e:
+        g.get_delta_w(0)
+    assert e.value.code == -3
+    # an out-of-range visiting-order entry is skipped and reported, not dereferenced
+    badperm = np.concatenate(perms).copy()
+    badperm[1] = 10**6
+    g.local_epoch_host_perm(badperm)
+    with pytest.raises(E) as e:
+        g.sync()
+    assert e.value.code == -4
+    g.sync()                                                      # flag cleared
+    g.aggregate()
+    assert g.gap()[2] >= 0
+    g.close()
+
+
+def test_set_state_resumes_a_run(mods):
+    """Uploading the oracle's (alpha, w) and continuing gives the oracle's next round."""
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "mini")
+    o = oracle_mod.OracleCoCoA.from_problem(p)
+    K = cfg["K"]
+    table = oracle_mod.assign_greedy(p.chunk_nnz(), K)
+    o.assign(K, table)
+    for r in range(3):
+        o.local_epoch(round_permutations(1, r, o.rows_per_solver()), keep_deltas=False)
+        o.aggregate()
+    g = binding.ChicleRound.from_problem(p, max_solvers=K)
+    g.assign(K, table)
+    for c in range(p.n_chunks):
+        r0, r1 = p.chunk_rows(c)
+        g.set_alpha(c, o.alpha[r0:r1])
+    g.set_w(o.w)
+    assert abs(g.gap()[2] - o.gap()[2]) <= 1e-5 * abs(o.gap()[2])
+    perms = round_permutations(1, 3, o.rows_per_solver())
+    dws = o.local_epoch(perms)
+    g.local_epoch(g.upload_perm(perms))
+    for k in range(K):
+        assert np.linalg.norm(g.get_delta_w(k) - dws[k]) <= TOL_DW * np.linalg.norm(dws[k])
+    g.close()
