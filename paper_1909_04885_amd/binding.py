@@ -49,6 +49,10 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         from .build import build_library
         build_library()
+    # PyTorch-ROCm carries its own HIP runtime (same soname as the system one).  Import it first so
+    # that this library binds to the runtime that owns the arena and the stream; two HIP runtimes in
+    # one process do not see each other's allocations.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
     sz = ctypes.c_size_t
