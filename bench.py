@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the CoCoA round on one MI355X.
+
+A step is one whole round: the local SDCA pass of all K solvers, the aggregation of their updates
+and the duality-gap evaluation, on a synthetic workload already resident in HBM (visiting orders
+included).  Prints one JSON line: whole-round throughput in stored matrix entries per second, the
+HBM roofline position of the dominant kernel (the local pass), and the CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(p, table, K):
+    """Bytes the local pass must move per launch: the matrix once, the per-row state once, and each
+    solver's touched part of its private vector in and out once (cache traffic is not counted).
+    CSR: 8 B per entry + 24 B per row (row offset, order entry, label, norm, alpha read and write)
+    + 8 B per distinct column a solver touches.  Dense: 4 B per entry + 20 B per row + 8 B per column
+    per solver."""
+    if p.dense:
+        return 4 * p.nnz + 20 * p.n + 8 * p.d * K
+    touched = 0
+    for k in range(K):
+        seen = np.zeros(p.d, dtype=bool)
+        for c in np.nonzero(table == k)[0]:
+            r0, r1 = p.chunk_rows(c)
+            seen[p.col[p.row_ptr[r0]:p.row_ptr[r1]]] = True
+        touched += int(seen.sum())
+    return 8 * p.nnz + 24 * p.n + 8 * touched
+
+
+def cpu_baseline(p, cfg, table, K, budget_s=15.0):
+    """The oracle as it stands, single-threaded, on whole rounds of the same workload until about
+    budget_s seconds of CPU work have been spent (at least one round)."""
+    import oracle
+    o = oracle.OracleCoCoA.from_problem(p)
+    o.assign(K, table)
+    from workloads import round_permutations
+    rounds, spent = 0, 0.0
+    while rounds < 1 or (spent < budget_s and rounds < cfg["rounds"]):
+        perms = round_permutations(cfg["seed"], rounds, o.rows_per_solver())
+        t0 = time.perf_counter()
+        o.local_epoch(perms, keep_deltas=False)
+        o.aggregate()
+        o.gap()
+        spent += time.perf_counter() - t0
+        rounds += 1
+    return {"value": p.nnz * rounds / spent, "unit": "nnz/s", "cores": 1, "kind": "oracle",
+            "sample": "%d whole rounds of the same workload (local pass + aggregate + gap), %.1f s" % (rounds, spent)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="sparse_zipf")
+    ap.add_argument("--size", default="full")
+    ap.add_argument("--solver", default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the K local solvers run concurrently on a single MI355X and "
+              "nothing here uses a second device; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1909_04885_amd as chicle
+    from workloads import get_config, make_problem, round_permutations
+
+    cfg = get_config(args.workload, args.size)
+    t0 = time.time()
+    p = make_problem(cfg)
+    K = cfg["K"]
+    table = chicle.balance(p.chunk_nnz(), K)
+    print("generated %s/%s: n=%d d=%d entries=%d chunks=%d K=%d in %.1fs" %
+          (args.workload, args.size, p.n, p.d, p.nnz, p.n_chunks, K, time.time() - t0), file=sys.stderr, flush=True)
+
+    g = chicle.ChicleRound.from_problem(p, max_solvers=K)
+    g.set_solver(args.solver)
+    g.assign(K, table)
+    rows = g.solver_rows()
+    total = args.warmup + args.steps
+    perms = [g.upload_perm(round_permutations(cfg["seed"], r, rows)) for r in range(total)]
+    g.set_profiling(True)
+    torch.cuda.synchronize()
+
+    for r in range(args.warmup):
+        g.local_epoch(perms[r]); g.aggregate(); g.gap()
+    torch.cuda.synchronize()
+    seg_ms = {"local_epoch": [], "aggregate": [], "gap": [], "epoch_gram": [], "epoch_chain": []}
+    gaps = []
+    t_start = time.perf_counter()
+    for r in range(args.warmup, total):
+        g.local_epoch(perms[r])
+        g.aggregate()
+        gaps.append(g.gap()[2])          # synchronises: the three scalars come back to the host
+        for s in seg_ms:                  # events of this round have completed
+            try:
+                seg_ms[s].append(g.last_kernel_ms(s))
+            except chicle.ChicleError:
+                pass                      # segment not part of this solver kind
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    epoch_ms = float(np.mean(seg_ms["local_epoch"]))
+    agg_ms = float(np.mean(seg_ms["aggregate"]))
+    gap_ms = float(np.mean(seg_ms["gap"]))
+    abytes = algorithmic_bytes(p, table, K)
+    achieved = abytes / (epoch_ms * 1e-3) / 1e9
+    agg_bytes = 4 * p.d * (2 * K + 2)
+    gap_bytes = (8 if not p.dense else 4) * p.nnz + 12 * p.n + 4 * p.d
+    out = {
+        "metric": "nnz_per_s_per_cocoa_round",
+        "value": p.nnz * args.steps / elapsed,
+        "unit": "nnz/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s/%s" % (args.workload, args.size), "n": p.n, "d": p.d, "entries": p.nnz,
+                   "K": K, "chunk_rows": cfg["chunk_rows"], "lambda": cfg["lam"], "loss": p.loss,
+                   "solver": args.solver},
+        "local_epoch": {"ms": epoch_ms, "nnz_per_s": p.nnz / (epoch_ms * 1e-3),
+                        "coord_updates_per_s": p.n / (epoch_ms * 1e-3),
+                        "gram_ms": float(np.mean(seg_ms["epoch_gram"])) if seg_ms["epoch_gram"] else None,
+                        "chain_ms": float(np.mean(seg_ms["epoch_chain"])) if seg_ms["epoch_chain"] else None},
+        "aggregate": {"ms": agg_ms, "GB_per_s": agg_bytes / (agg_ms * 1e-3) / 1e9,
+                      "frac_hbm_peak": agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "gap": {"ms": gap_ms, "GB_per_s": gap_bytes / (gap_ms * 1e-3) / 1e9,
+                "frac_hbm_peak": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "first": gaps[0], "last": gaps[-1]},
+        "roofline": {"kernel": "local_epoch", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": abytes},
+    }
+    g.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p, cfg, table, K)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

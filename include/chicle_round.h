@@ -31,6 +31,8 @@
  *     chicle_last_error() gives a message for the last failure on that context;
  *   - "host" pointers are ordinary CPU memory, read or written before the call returns; the caller
  *     keeps ownership;  "device" pointers are HBM addresses valid on the context's GPU;
+ *   - columns are addressed by the caller's ids in every call; inside the chunk store sparse columns
+ *     are renumbered by popularity (done once, at the first assign), which the get/set calls undo;
  *   - the library allocates no device memory: it carves everything out of the arena handed to
  *     chicle_create (size it with chicle_arena_bytes); the arena and the HIP stream are borrowed for
  *     the lifetime of the context; all work is enqueued on that stream;
@@ -151,7 +153,7 @@ int chicle_aggregate(chicle_ctx *ctx);
 int chicle_gap(chicle_ctx *ctx, double *primal, double *dual, double *gap);
 
 /* State access (host arrays of d floats / n_rows-of-that-chunk floats).  get_* synchronise.
- * set_w and set_alpha are legal in READY/LOADING only; get_delta_w in EPOCH_DONE only:
+ * set_alpha is legal in READY/LOADING, set_w in READY; get_delta_w in EPOCH_DONE only:
  * solver >= 0 gives Delta w_solver = (v_solver - w)/sigma, solver = -1 gives sum_k Delta w_k. */
 int chicle_get_w(chicle_ctx *ctx, float *w_out);
 int chicle_set_w(chicle_ctx *ctx, const float *w_in);
@@ -160,8 +162,15 @@ int chicle_get_alpha(chicle_ctx *ctx, int32_t chunk_id, float *alpha_out);
 int chicle_set_alpha(chicle_ctx *ctx, int32_t chunk_id, const float *alpha_in);
 int chicle_get_assignment(chicle_ctx *ctx, int32_t *chunk_to_solver_out, int32_t *K_out);
 
-/* Device address of w (d floats), for callers that keep everything on the GPU. */
-int chicle_w_device(chicle_ctx *ctx, const float **w_device_out);
+/* Diagnostic: run only the Gram-block kernel of the batched solver for the given visiting orders and
+ * copy its output to the host.  Blocks of 64 consecutive steps of a solver form one tile of 128 x 64
+ * floats laid out [jp][i]: T[jp][i] couples step i of the block with step jp of the previous block
+ * (jp < 64) or with step jp - 64 of the same block (entries with jp - 64 >= i are zero);
+ * T = -y_i y_j (x_i . x_j) / |x_i|^2 for hinge, -(x_i . x_j) / (lambda n / sigma + |x_i|^2) for squared loss.
+ * Tiles are ordered by solver, then by block.  tiles_out may be NULL to query *n_tiles_out only.
+ * Legal in READY.  Errors: EINVAL (data not eligible for the batched solver, capacity), ESTATE. */
+int chicle_debug_gram(chicle_ctx *ctx, const int32_t *perm_device, float *tiles_out,
+                      int64_t capacity_floats, int32_t *n_tiles_out);
 
 /* Wait for the stream; report any deferred kernel error. */
 int chicle_sync(chicle_ctx *ctx);

@@ -26,7 +26,7 @@ EXPORTS = [
     "chicle_balance", "chicle_assign", "chicle_solver_rows", "chicle_set_solver",
     "chicle_local_epoch", "chicle_local_epoch_host_perm", "chicle_aggregate", "chicle_gap",
     "chicle_get_w", "chicle_set_w", "chicle_get_delta_w", "chicle_get_alpha", "chicle_set_alpha",
-    "chicle_get_assignment", "chicle_w_device", "chicle_sync", "chicle_set_profiling",
+    "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
 ]
 
@@ -75,7 +75,7 @@ def load_library():
         "chicle_get_alpha": (ctypes.c_int, [vp, i32, vp]),
         "chicle_set_alpha": (ctypes.c_int, [vp, i32, vp]),
         "chicle_get_assignment": (ctypes.c_int, [vp, vp, ctypes.POINTER(i32)]),
-        "chicle_w_device": (ctypes.c_int, [vp, ctypes.POINTER(vp)]),
+        "chicle_debug_gram": (ctypes.c_int, [vp, vp, vp, i64, ctypes.POINTER(i32)]),
         "chicle_sync": (ctypes.c_int, [vp]),
         "chicle_set_profiling": (ctypes.c_int, [vp, i32]),
         "chicle_last_kernel_ms": (ctypes.c_int, [vp, i32, ctypes.POINTER(ctypes.c_float)]),
@@ -257,10 +257,14 @@ class ChicleRound:
             raise ChicleError(EINVAL, "alpha needs one entry per row of the chunk")
         self._check(self._L.chicle_set_alpha(self._h, chunk_id, _ptr(a)))
 
-    def w_device(self) -> int:
-        p = ctypes.c_void_p()
-        self._check(self._L.chicle_w_device(self._h, ctypes.byref(p)))
-        return p.value
+    def debug_gram(self, perm_device) -> np.ndarray:
+        """Tiles of the batched solver's Gram kernel, shape [n_tiles, 128, 64]."""
+        n = ctypes.c_int32()
+        ptr = ctypes.c_void_p(perm_device.data_ptr())
+        self._check(self._L.chicle_debug_gram(self._h, ptr, None, 0, ctypes.byref(n)))
+        out = np.empty((n.value, 128, 64), dtype=np.float32)
+        self._check(self._L.chicle_debug_gram(self._h, ptr, _ptr(out), out.size, ctypes.byref(n)))
+        return out
 
     def sync(self):
         self._check(self._L.chicle_sync(self._h))

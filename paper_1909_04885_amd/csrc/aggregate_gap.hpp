@@ -7,51 +7,48 @@
 
 namespace chicle {
 
-// v_k <- w for k < K (a solver fetching the model).
-__global__ __launch_bounds__(256) void seed_private(const float *__restrict__ w, float *v_all,
-                                                    int64_t ld_v, int64_t d, int K)
+// u_k <- 0 for k < K (a solver fetching the model starts with no update of its own).
+__global__ __launch_bounds__(256) void clear_private(float *u_all, int64_t ld_v, int64_t d4, int K)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
-        const float x = w[j];
-        for (int k = 0; k < K; ++k) v_all[(int64_t)k * ld_v + j] = x;
-    }
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d4; j += stride)
+        for (int k = 0; k < K; ++k) reinterpret_cast<float4 *>(u_all + (int64_t)k * ld_v)[j] = z;
 }
 
-// w <- w + sum_k Delta w_k with Delta w_k = (v_k - w)/sigma, then v_k <- w for all k.
+// w <- w + sum_k Delta w_k with Delta w_k = u_k / sigma, then u_k <- 0 for all k (merge, broadcast).
 // One pass: reads K + 1 vectors, writes K + 1 vectors, four columns per thread (ld_v and the
 // buffers are 16-byte aligned; d is handled up to its padded length, the padding holds zeros).
-__global__ __launch_bounds__(256) void aggregate_broadcast(float *w, float *v_all, int64_t ld_v,
+__global__ __launch_bounds__(256) void aggregate_broadcast(float *w, float *u_all, int64_t ld_v,
                                                            int64_t d4, int K, float inv_sigma)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     float4 *w4 = reinterpret_cast<float4 *>(w);
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d4; j += stride) {
-        const float4 x = w4[j];
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 acc = z;
         for (int k = 0; k < K; ++k) {
-            const float4 vk = reinterpret_cast<const float4 *>(v_all + (int64_t)k * ld_v)[j];
-            acc.x += vk.x - x.x; acc.y += vk.y - x.y; acc.z += vk.z - x.z; acc.w += vk.w - x.w;
+            float4 *uk = reinterpret_cast<float4 *>(u_all + (int64_t)k * ld_v) + j;
+            const float4 x = *uk;
+            acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+            *uk = z;
         }
-        float4 o;
-        o.x = x.x + acc.x * inv_sigma; o.y = x.y + acc.y * inv_sigma;
-        o.z = x.z + acc.z * inv_sigma; o.w = x.w + acc.w * inv_sigma;
+        float4 o = w4[j];
+        o.x += acc.x * inv_sigma; o.y += acc.y * inv_sigma;
+        o.z += acc.z * inv_sigma; o.w += acc.w * inv_sigma;
         w4[j] = o;
-        for (int k = 0; k < K; ++k) reinterpret_cast<float4 *>(v_all + (int64_t)k * ld_v)[j] = o;
     }
 }
 
 // out <- Delta w_solver, or sum_k Delta w_k when solver < 0 (read-back helper).
-__global__ __launch_bounds__(256) void delta_w_out(const float *__restrict__ w, const float *v_all,
-                                                   int64_t ld_v, int64_t d, int K, int solver,
-                                                   float inv_sigma, float *out)
+__global__ __launch_bounds__(256) void delta_w_out(const float *u_all, int64_t ld_v, int64_t d, int K,
+                                                   int solver, float inv_sigma, float *out)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
-        const float x = w[j];
         float acc = 0.f;
-        if (solver >= 0) acc = v_all[(int64_t)solver * ld_v + j] - x;
-        else for (int k = 0; k < K; ++k) acc += v_all[(int64_t)k * ld_v + j] - x;
+        if (solver >= 0) acc = u_all[(int64_t)solver * ld_v + j];
+        else for (int k = 0; k < K; ++k) acc += u_all[(int64_t)k * ld_v + j];
         out[j] = acc * inv_sigma;
     }
 }
@@ -78,7 +75,8 @@ __device__ __forceinline__ void block_sum2_store(double a, double b, double *out
     }
 }
 
-// Per-row loss and conjugate terms of the gap, sparse rows.  LPR lanes cooperate on one row
+// Per-row loss and conjugate terms of the gap, sparse rows; also leaves z_i = x_i . w in the chunk
+// (zw) for the next local pass.  LPR lanes cooperate on one row
 // (LPR divides 64).  Work items are blocks of 256/LPR rows of one chunk; item_prefix[c] = first
 // item of chunk c.  Each workgroup writes one partial (loss sum, conjugate sum) in double.
 //   hinge   : loss = max(0, 1 - y z),   conj = loss^*(-a) = -a
@@ -107,6 +105,7 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
         if (live && sub == 0) {
+            ch.zw[r] = z;
             const float y = ch.y[r], a = ch.alpha[r];
             if (LOSS == 0) {
                 s_loss += (double)fmaxf(0.f, 1.f - y * z);
@@ -146,6 +145,7 @@ __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
         if (live && sub == 0) {
+            ch.zw[r] = z;
             const float y = ch.y[r], a = ch.alpha[r];
             if (LOSS == 0) {
                 s_loss += (double)fmaxf(0.f, 1.f - y * z);

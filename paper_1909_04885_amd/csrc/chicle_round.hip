@@ -8,12 +8,15 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <numeric>
 #include <string>
 #include <vector>
 
 #include "../../include/chicle_round.h"
 #include "aggregate_gap.hpp"
 #include "device_types.hpp"
+#include "layout.hpp"
+#include "sdca_batched.hpp"
 #include "sdca_rowwise.hpp"
 
 using namespace chicle;
@@ -25,11 +28,14 @@ constexpr int GAP_PARTS = 4096;        // workgroups (and partial sums) of the g
 constexpr int WSQ_PARTS = 512;
 constexpr int MAX_LIST_LDS = 4096;     // chunks one solver may own (its lists are staged in LDS)
 constexpr int DENSE_V_LDS_MAX_D = 8192;
+constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
+constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline int64_t pad_d(int64_t d) { return (d + 63) / 64 * 64; }
+inline int64_t tiles_cap(int64_t n_total, int32_t max_solvers) { return n_total / BATCH + max_solvers + 1; }
 
 struct Seg {
     hipEvent_t start = nullptr, stop = nullptr;
@@ -50,7 +56,6 @@ struct chicle_ctx {
     char *arena = nullptr;
     size_t arena_bytes = 0, used = 0;
     hipStream_t stream = nullptr;
-    int device = 0;
     State state = ST_LOADING;
     int solver_kind = CHICLE_SOLVER_AUTO;
 
@@ -58,7 +63,17 @@ struct chicle_ctx {
     ChunkDev *chunks_dev = nullptr;
     SolverDev *solvers_dev = nullptr;
     int32_t *solver_chunks_dev = nullptr, *solver_prefix_dev = nullptr, *item_prefix_dev = nullptr;
-    float *w = nullptr, *v = nullptr, *dw_tmp = nullptr;
+    float *w = nullptr;        // shared vector (internal column order)
+    float *u = nullptr;        // private vectors as differences u_k = v_k - w, max_solvers x ld_v
+    float *tmp_a = nullptr, *tmp_b = nullptr;   // d floats each: staging of host transfers
+    int32_t *rank_of = nullptr, *col_of = nullptr;   // column renumbering tables (device)
+    bool renumbered = false;
+    int32_t max_row_len = 0;
+    float *tiles = nullptr;
+    int32_t *tile_solver_dev = nullptr;
+    int64_t max_tiles = 0;
+    int32_t n_tiles = 0;
+    bool zw_valid = true;      // zw = X w holds trivially for w = 0 after loading
     int32_t *perm_stage = nullptr;
     double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
            *gap_out = nullptr;
@@ -119,8 +134,11 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(SolverDev) * (size_t)max_solvers);
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);
     s += align_up(sizeof(int32_t) * ((size_t)n_chunks + 1));
-    s += align_up(sizeof(float) * (size_t)ld) * 2;                       // w, dw_tmp
+    s += align_up(sizeof(float) * (size_t)ld) * 3;                       // w, tmp_a, tmp_b
     s += align_up(sizeof(float) * (size_t)ld * (size_t)max_solvers);     // private vectors
+    s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
+    s += align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
+    s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
     s += align_up(sizeof(int32_t) * (size_t)n_total);                    // perm staging
     s += 2 * align_up(sizeof(double) * GAP_PARTS) + 2 * align_up(sizeof(double) * WSQ_PARTS);
     s += align_up(sizeof(double) * 4);
@@ -133,10 +151,10 @@ size_t chunk_bytes(bool dense, int64_t n_rows, int64_t entries)
     size_t s = 0;
     if (!dense) {
         s += align_up(sizeof(int32_t) * (size_t)(n_rows + 1));
-        s += align_up(sizeof(int32_t) * (size_t)entries);
+        s += align_up(sizeof(int32_t) * (size_t)std::max<int64_t>(entries, 1));
     }
-    s += align_up(sizeof(float) * (size_t)entries);
-    s += 3 * align_up(sizeof(float) * (size_t)n_rows);
+    s += align_up(sizeof(float) * (size_t)std::max<int64_t>(entries, 1));
+    s += 4 * align_up(sizeof(float) * (size_t)n_rows);
     return s;
 }
 
@@ -174,12 +192,12 @@ int grid_for(int64_t items, int per_block, int cap)
     return (int)g;
 }
 
-int seed_all(chicle_ctx *c)
+int clear_all_private(chicle_ctx *c)
 {
     if (c->K <= 0) return CHICLE_OK;
-    const int g = grid_for(c->d, 256, 2048);
-    hipLaunchKernelGGL(seed_private, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v,
-                       (int64_t)c->d, c->K);
+    const int64_t d4 = c->ld_v / 4;
+    hipLaunchKernelGGL(clear_private, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->u,
+                       c->ld_v, d4, c->K);
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;
 }
@@ -195,6 +213,11 @@ RoundScalars scalars(const chicle_ctx *c)
     return s;
 }
 
+bool batched_eligible(const chicle_ctx *c)
+{
+    return !c->dense && c->max_row_len <= GRAM_MAX_ROW && c->max_list <= BATCHED_MAX_LIST;
+}
+
 template <int LOSS>
 int launch_rowwise(chicle_ctx *c, const int32_t *perm)
 {
@@ -206,35 +229,68 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
         if (v_lds)
             hipLaunchKernelGGL((sdca_rowwise_dense<LOSS, 64, true>), dim3(c->K), dim3(64), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->v, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
+                               perm, c->u, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
         else
             hipLaunchKernelGGL((sdca_rowwise_dense<LOSS, 256, false>), dim3(c->K), dim3(256), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->v, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
+                               perm, c->u, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
     } else {
         const double avg = c->n_total ? (double)c->total_entries / (double)c->n_total : 0.0;
         if (avg <= 96.0)
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64>), dim3(c->K), dim3(64), list_bytes, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->v, c->ld_v, sc, c->err_dev);
+                               perm, c->u, c->ld_v, sc, c->err_dev);
         else
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 256>), dim3(c->K), dim3(256), list_bytes, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->v, c->ld_v, sc, c->err_dev);
+                               perm, c->u, c->ld_v, sc, c->err_dev);
     }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;
 }
 
-template <int LOSS, int LPR>
+template <int LOSS>
+int launch_gram(chicle_ctx *c, const int32_t *perm)
+{
+    const RoundScalars sc = scalars(c);
+    if (c->n_tiles > 0)
+        hipLaunchKernelGGL((gram_tiles_merge<LOSS>), dim3(c->n_tiles), dim3(256), 0, c->stream, c->chunks_dev,
+                           c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm,
+                           c->tile_solver_dev, c->tiles, sc.c, c->err_dev);
+    HIP_TRY(c, hipGetLastError());
+    return CHICLE_OK;
+}
+
+template <int LOSS>
+int launch_batched(chicle_ctx *c, const int32_t *perm)
+{
+    const RoundScalars sc = scalars(c);
+    seg_begin(c, CHICLE_SEG_EPOCH_GRAM);
+    int rc = launch_gram<LOSS>(c, perm);
+    seg_end(c, CHICLE_SEG_EPOCH_GRAM);
+    if (rc) return rc;
+    const int ml = std::max(c->max_list, 1);
+    const size_t sh = sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml;
+    auto kern = sdca_batched_csr<LOSS>;
+    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+    seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+    hipLaunchKernelGGL(kern, dim3(c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
+                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles, c->u, c->ld_v, ml, sc,
+                       c->err_dev);
+    seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    HIP_TRY(c, hipGetLastError());
+    return CHICLE_OK;
+}
+
+template <int LOSS, int LPRG>
 void launch_gap_rows(chicle_ctx *c, int grid)
 {
     if (c->dense)
-        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPR>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
                            c->item_prefix_dev, c->n_chunks, c->gap_items, (int)c->d, c->w, c->part_loss,
                            c->part_conj);
     else
-        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPR>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
                            c->item_prefix_dev, c->n_chunks, c->gap_items, c->w, c->part_loss, c->part_conj);
 }
 
@@ -250,6 +306,17 @@ void launch_gap_lpr(chicle_ctx *c, int grid)
     }
 }
 
+// The row pass of the gap: z_i = x_i . w into the chunks, loss and conjugate partial sums.
+int run_row_pass(chicle_ctx *c, int *grid_out)
+{
+    const int grid = std::max(1, std::min(c->gap_items, GAP_PARTS));
+    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, grid); else launch_gap_lpr<1>(c, grid);
+    HIP_TRY(c, hipGetLastError());
+    c->zw_valid = true;
+    if (grid_out) *grid_out = grid;
+    return CHICLE_OK;
+}
+
 int choose_lpr(double avg_row_len)
 {
     if (avg_row_len <= 6) return 4;
@@ -259,11 +326,11 @@ int choose_lpr(double avg_row_len)
     return 64;
 }
 
-// Greedy table shared by chicle_balance; integers only.
-bool greedy_table(const int64_t *load, int32_t n_chunks, int32_t K, const int32_t *speed, int32_t *out)
+// Greedy table of chicle_balance; integers only.
+void greedy_table(const int64_t *load, int32_t n_chunks, int32_t K, const int32_t *speed, int32_t *out)
 {
     std::vector<int32_t> order(n_chunks);
-    for (int32_t i = 0; i < n_chunks; ++i) order[i] = i;
+    std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t a, int32_t b) { return load[a] > load[b]; });
     std::vector<int64_t> L(K, 0);
@@ -277,7 +344,31 @@ bool greedy_table(const int64_t *load, int32_t n_chunks, int32_t K, const int32_
         out[c] = best;
         L[best] += load[c];
     }
-    return true;
+}
+
+// Once, when every chunk is in HBM: renumber the columns by popularity and re-sort the rows.
+int renumber_columns(chicle_ctx *c)
+{
+    int32_t *count = c->rank_of;   // the table is built in place of the counts
+    HIP_TRY(c, hipMemsetAsync(count, 0, sizeof(int32_t) * (size_t)c->d, c->stream));
+    hipLaunchKernelGGL(count_columns, dim3(c->n_chunks), dim3(256), 0, c->stream, c->chunks_dev, count);
+    HIP_TRY(c, hipGetLastError());
+    std::vector<int32_t> cnt(c->d), order(c->d), rank(c->d);
+    HIP_TRY(c, hipMemcpyAsync(cnt.data(), count, sizeof(int32_t) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return cnt[a] > cnt[b]; });
+    for (int32_t r = 0; r < c->d; ++r) rank[order[r]] = r;
+    HIP_TRY(c, hipMemcpyAsync(c->rank_of, rank.data(), sizeof(int32_t) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->col_of, order.data(), sizeof(int32_t) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
+    int max_rows = 1;
+    for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
+    hipLaunchKernelGGL(renumber_rows, dim3(grid_for(max_rows, 256, 64), c->n_chunks), dim3(256), 0, c->stream,
+                       c->chunks_dev, c->rank_of);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->renumbered = true;
+    return CHICLE_OK;
 }
 
 }  // namespace
@@ -290,12 +381,12 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
     if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
     size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
-    const size_t per_chunk_slack = 6 * ALIGN;
+    const size_t per_chunk_slack = 8 * ALIGN;
     if (dense)
-        s += sizeof(float) * (size_t)total_entries + 3 * sizeof(float) * (size_t)n_total;
+        s += sizeof(float) * (size_t)total_entries + 4 * sizeof(float) * (size_t)n_total;
     else
-        s += (sizeof(int32_t) + sizeof(float)) * (size_t)total_entries +
-             sizeof(int32_t) * ((size_t)n_total + (size_t)n_chunks) + 3 * sizeof(float) * (size_t)n_total;
+        s += (sizeof(int32_t) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
+             sizeof(int32_t) * ((size_t)n_total + (size_t)n_chunks) + 4 * sizeof(float) * (size_t)n_total;
     s += per_chunk_slack * (size_t)n_chunks;
     return s + ALIGN;
 }
@@ -319,7 +410,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->total_entries = total_entries;
     c->arena = (char *)device_arena; c->arena_bytes = arena_bytes;
     c->stream = (hipStream_t)hip_stream;
-    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CHICLE_EDEVICE; }
+    c->max_tiles = tiles_cap(n_total, max_solvers);
 
     c->chunks_dev = (ChunkDev *)carve(c, sizeof(ChunkDev) * (size_t)n_chunks);
     c->solvers_dev = (SolverDev *)carve(c, sizeof(SolverDev) * (size_t)max_solvers);
@@ -327,8 +418,13 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->solver_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     c->item_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * ((size_t)n_chunks + 1));
     c->w = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
-    c->dw_tmp = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
-    c->v = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
+    c->tmp_a = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
+    c->tmp_b = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
+    c->u = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
+    c->rank_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
+    c->col_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
+    c->tiles = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
+    c->tile_solver_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->max_tiles);
     c->perm_stage = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
     c->part_loss = (double *)carve(c, sizeof(double) * GAP_PARTS);
     c->part_conj = (double *)carve(c, sizeof(double) * GAP_PARTS);
@@ -341,8 +437,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
     bool ok = hipMemsetAsync(c->w, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
-              hipMemsetAsync(c->dw_tmp, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
-              hipMemsetAsync(c->v, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->tmp_a, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->tmp_b, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
               hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess;
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
@@ -353,7 +450,6 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
 
 static int load_common(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, int64_t entries)
 {
-    if (!c) return CHICLE_EINVAL;
     if (c->state != ST_LOADING) return fail(c, CHICLE_ESTATE, "chunks can only be loaded before the first assign");
     if (chunk_id < 0 || chunk_id >= c->n_chunks) return fail(c, CHICLE_EINVAL, "chunk id %d out of range", chunk_id);
     if (c->loaded[chunk_id]) return fail(c, CHICLE_EINVAL, "chunk %d already loaded", chunk_id);
@@ -386,23 +482,23 @@ static int check_state_arrays(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, c
 static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const float *y, const float *alpha0,
                        const std::vector<float> &q)
 {
-    const int32_t n_rows = ch.n_rows;
-    float *yd = (float *)carve(c, sizeof(float) * (size_t)n_rows);
-    float *ad = (float *)carve(c, sizeof(float) * (size_t)n_rows);
-    float *qd = (float *)carve(c, sizeof(float) * (size_t)n_rows);
-    if (!qd) return fail(c, CHICLE_ENOMEM, "chunk store full");
-    ch.y = yd; ch.alpha = ad; ch.q = qd;
-    HIP_TRY(c, hipMemcpyAsync(yd, y, sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
-    if (alpha0)
-        HIP_TRY(c, hipMemcpyAsync(ad, alpha0, sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
-    else
-        HIP_TRY(c, hipMemsetAsync(ad, 0, sizeof(float) * (size_t)n_rows, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(qd, q.data(), sizeof(float) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
+    const size_t nb = sizeof(float) * (size_t)ch.n_rows;
+    float *yd = (float *)carve(c, nb);
+    float *ad = (float *)carve(c, nb);
+    float *qd = (float *)carve(c, nb);
+    float *zd = (float *)carve(c, nb);
+    if (!zd) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    ch.y = yd; ch.alpha = ad; ch.q = qd; ch.zw = zd;
+    HIP_TRY(c, hipMemcpyAsync(yd, y, nb, hipMemcpyHostToDevice, c->stream));
+    if (alpha0) HIP_TRY(c, hipMemcpyAsync(ad, alpha0, nb, hipMemcpyHostToDevice, c->stream));
+    else HIP_TRY(c, hipMemsetAsync(ad, 0, nb, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(qd, q.data(), nb, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemsetAsync(zd, 0, nb, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));   // host arrays are the caller's again on return
     c->chunks[chunk_id] = ch;
     c->loaded[chunk_id] = 1;
     c->n_loaded += 1;
-    c->rows_loaded += n_rows;
+    c->rows_loaded += ch.n_rows;
     c->entries_loaded += ch.nnz;
     return CHICLE_OK;
 }
@@ -423,6 +519,7 @@ int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const
     rc = check_state_arrays(c, chunk_id, n_rows, y, alpha0);
     if (rc) return rc;
     std::vector<float> q(n_rows);
+    int32_t longest = 0;
     for (int32_t r = 0; r < n_rows; ++r) {
         double s = 0.0;
         for (int32_t p = row_ptr[r]; p < row_ptr[r + 1]; ++p) {
@@ -432,6 +529,7 @@ int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const
             s += (double)val[p] * (double)val[p];
         }
         q[r] = (float)s;
+        longest = std::max(longest, row_ptr[r + 1] - row_ptr[r]);
     }
     ChunkDev ch{};
     ch.n_rows = n_rows; ch.nnz = nnz;
@@ -445,7 +543,9 @@ int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const
         HIP_TRY(c, hipMemcpyAsync(cd, col, sizeof(int32_t) * (size_t)nnz, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(vd, val, sizeof(float) * (size_t)nnz, hipMemcpyHostToDevice, c->stream));
     }
-    return finish_load(c, chunk_id, ch, y, alpha0, q);
+    rc = finish_load(c, chunk_id, ch, y, alpha0, q);
+    if (rc == CHICLE_OK) c->max_row_len = std::max(c->max_row_len, longest);
+    return rc;
 }
 
 int chicle_load_chunk_dense(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const float *X,
@@ -475,7 +575,9 @@ int chicle_load_chunk_dense(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, con
     if (!xd) return fail(c, CHICLE_ENOMEM, "chunk store full");
     ch.val = xd;
     HIP_TRY(c, hipMemcpyAsync(xd, X, sizeof(float) * (size_t)entries, hipMemcpyHostToDevice, c->stream));
-    return finish_load(c, chunk_id, ch, y, alpha0, q);
+    rc = finish_load(c, chunk_id, ch, y, alpha0, q);
+    if (rc == CHICLE_OK) c->max_row_len = c->d;
+    return rc;
 }
 
 int chicle_balance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const int32_t *speed_q,
@@ -512,18 +614,25 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
 
     std::vector<SolverDev> sol(K);
     std::vector<int32_t> list(c->n_chunks), prefix(c->n_chunks);
-    int32_t pos = 0;
+    int32_t pos = 0, tile = 0;
     int64_t perm_off = 0;
     for (int32_t k = 0; k < K; ++k) {
-        sol[k].list_begin = pos; sol[k].n_chunks = count[k]; sol[k].perm_off = perm_off; sol[k].pad_ = 0;
+        sol[k].list_begin = pos; sol[k].n_chunks = count[k]; sol[k].perm_off = perm_off;
         int32_t rows = 0;
         for (int32_t i = 0; i < c->n_chunks; ++i) {        // ascending chunk id
             if (chunk_to_solver[i] != k) continue;
             list[pos] = i; prefix[pos] = rows; rows += c->chunks[i].n_rows; ++pos;
         }
         sol[k].n_rows = rows;
+        sol[k].tile_begin = tile;
+        tile += (rows + BATCH - 1) / BATCH;
         perm_off += rows;
     }
+    if (tile > c->max_tiles) return fail(c, CHICLE_ENOMEM, "tile scratch too small");
+    std::vector<int32_t> tile_solver(std::max(tile, 1));
+    for (int32_t k = 0; k < K; ++k)
+        for (int32_t t = sol[k].tile_begin; t < sol[k].tile_begin + (sol[k].n_rows + BATCH - 1) / BATCH; ++t)
+            tile_solver[t] = k;
     // work items of the gap kernels: blocks of 256/LPR rows inside a chunk
     const double avg = c->dense ? (double)c->d : (double)c->total_entries / (double)c->n_total;
     c->gap_lpr = choose_lpr(avg);
@@ -532,21 +641,26 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     for (int32_t i = 0; i < c->n_chunks; ++i)
         items[i + 1] = items[i] + (c->chunks[i].n_rows + rows_per_item - 1) / rows_per_item;
 
-    // Stream order keeps earlier kernels ahead of these copies; the host vectors are pageable, so the
-    // copies have consumed them when the calls return, but wait anyway before they go out of scope.
+    // Stream order keeps earlier kernels ahead of these copies; wait before the host vectors go away.
     HIP_TRY(c, hipMemcpyAsync(c->chunks_dev, c->chunks.data(), sizeof(ChunkDev) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->solvers_dev, sol.data(), sizeof(SolverDev) * (size_t)K, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->solver_chunks_dev, list.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->solver_prefix_dev, prefix.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->item_prefix_dev, items.data(), sizeof(int32_t) * ((size_t)c->n_chunks + 1), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->tile_solver_dev, tile_solver.data(), sizeof(int32_t) * (size_t)tile, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->state == ST_LOADING && !c->dense && c->max_row_len <= RENUMBER_MAX_ROW) {
+        const int rc = renumber_columns(c);
+        if (rc) return rc;
+    }
     c->K = K;
     c->chunk_to_solver.assign(chunk_to_solver, chunk_to_solver + c->n_chunks);
     c->solvers = sol;
     c->max_list = max_list;
+    c->n_tiles = tile;
     c->gap_items = items[c->n_chunks];
     c->state = ST_READY;
-    return seed_all(c);
+    return clear_all_private(c);
 }
 
 int chicle_solver_rows(chicle_ctx *c, int64_t *rows_out)
@@ -560,8 +674,8 @@ int chicle_solver_rows(chicle_ctx *c, int64_t *rows_out)
 int chicle_set_solver(chicle_ctx *c, int32_t kind)
 {
     if (!c) return CHICLE_EINVAL;
-    if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE)
-        return fail(c, CHICLE_EINVAL, "solver kind %d not available", kind);
+    if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE && kind != CHICLE_SOLVER_BATCHED)
+        return fail(c, CHICLE_EINVAL, "unknown solver kind %d", kind);
     c->solver_kind = kind;
     return CHICLE_OK;
 }
@@ -571,10 +685,26 @@ int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
     if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
     if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
+    bool batched = false;
+    if (c->solver_kind == CHICLE_SOLVER_BATCHED) {
+        if (!batched_eligible(c))
+            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver", GRAM_MAX_ROW, BATCHED_MAX_LIST);
+        batched = true;
+    } else if (c->solver_kind == CHICLE_SOLVER_AUTO) {
+        batched = batched_eligible(c);
+    }
     seg_begin(c, CHICLE_SEG_LOCAL_EPOCH);
-    seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
-    const int rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device) : launch_rowwise<1>(c, perm_device);
-    seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    int rc = CHICLE_OK;
+    if (!c->zw_valid) rc = run_row_pass(c, nullptr);     // x_i . w for the current w
+    if (rc == CHICLE_OK) {
+        if (batched) {
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device) : launch_batched<1>(c, perm_device);
+        } else {
+            seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device) : launch_rowwise<1>(c, perm_device);
+            seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+        }
+    }
     seg_end(c, CHICLE_SEG_LOCAL_EPOCH);
     if (rc) return rc;
     c->state = ST_EPOCH_DONE;
@@ -597,11 +727,11 @@ int chicle_aggregate(chicle_ctx *c)
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "no local epoch pending");
     seg_begin(c, CHICLE_SEG_AGGREGATE);
     const int64_t d4 = c->ld_v / 4;
-    const int g = grid_for(d4, 256, 4096);
-    hipLaunchKernelGGL(aggregate_broadcast, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v, d4,
-                       c->K, (float)(1.0 / (double)c->K));
+    hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w,
+                       c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
     seg_end(c, CHICLE_SEG_AGGREGATE);
     HIP_TRY(c, hipGetLastError());
+    c->zw_valid = false;
     c->state = ST_READY;
     return CHICLE_OK;
 }
@@ -611,8 +741,9 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, "gap is defined on the aggregated state");
     seg_begin(c, CHICLE_SEG_GAP);
-    const int grid = std::max(1, std::min(c->gap_items, GAP_PARTS));
-    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, grid); else launch_gap_lpr<1>(c, grid);
+    int grid = 1;
+    int rc = run_row_pass(c, &grid);
+    if (rc) return rc;
     const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
     hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w, (int64_t)c->d, c->part_wsq, c->part_unused);
     hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, c->part_loss, c->part_conj, grid,
@@ -621,7 +752,7 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     HIP_TRY(c, hipGetLastError());
     double h[3];
     HIP_TRY(c, hipMemcpyAsync(h, c->gap_out, sizeof h, hipMemcpyDeviceToHost, c->stream));
-    const int rc = check_deferred(c);   // synchronises
+    rc = check_deferred(c);   // synchronises
     if (rc) return rc;
     const double n = (double)c->n_total;
     const double P = 0.5 * c->lambda * h[2] + h[0] / n;
@@ -632,20 +763,37 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     return CHICLE_OK;
 }
 
+// d floats in internal order on the device -> caller's order on the host.
+static int read_vector(chicle_ctx *c, const float *src_internal, float scale, float *host_out)
+{
+    hipLaunchKernelGGL(to_caller_order, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream,
+                       src_internal, c->renumbered ? c->col_of : (const int32_t *)nullptr, (int64_t)c->d,
+                       scale, c->tmp_b);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(host_out, c->tmp_b, sizeof(float) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
+    return check_deferred(c);
+}
+
 int chicle_get_w(chicle_ctx *c, float *w_out)
 {
     if (!c || !w_out) return CHICLE_EINVAL;
-    HIP_TRY(c, hipMemcpyAsync(w_out, c->w, sizeof(float) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
-    return check_deferred(c);
+    return read_vector(c, c->w, 1.0f, w_out);
 }
 
 int chicle_set_w(chicle_ctx *c, const float *w_in)
 {
     if (!c || !w_in) return CHICLE_EINVAL;
     if (c->state == ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "aggregate first");
-    HIP_TRY(c, hipMemcpyAsync(c->w, w_in, sizeof(float) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
+    if (c->state == ST_LOADING) return fail(c, CHICLE_ESTATE, "assign first (the column order is fixed at the first assign)");
+    for (int32_t j = 0; j < c->d; ++j)
+        if (!std::isfinite(w_in[j])) return fail(c, CHICLE_EINVAL, "w not finite at %d", j);
+    HIP_TRY(c, hipMemcpyAsync(c->tmp_b, w_in, sizeof(float) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
+    hipLaunchKernelGGL(from_caller_order, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->tmp_b,
+                       c->renumbered ? c->col_of : (const int32_t *)nullptr, (int64_t)c->d, c->w);
+    HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return c->state == ST_READY ? seed_all(c) : CHICLE_OK;
+    c->zw_valid = false;
+    return CHICLE_OK;
 }
 
 int chicle_get_delta_w(chicle_ctx *c, int32_t solver, float *dw_out)
@@ -653,12 +801,10 @@ int chicle_get_delta_w(chicle_ctx *c, int32_t solver, float *dw_out)
     if (!c || !dw_out) return CHICLE_EINVAL;
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "updates exist only between local_epoch and aggregate");
     if (solver < -1 || solver >= c->K) return fail(c, CHICLE_EINVAL, "solver %d, K=%d", solver, c->K);
-    const int g = grid_for(c->d, 256, 4096);
-    hipLaunchKernelGGL(delta_w_out, dim3(g), dim3(256), 0, c->stream, c->w, c->v, c->ld_v, (int64_t)c->d,
-                       c->K, solver, (float)(1.0 / (double)c->K), c->dw_tmp);
+    hipLaunchKernelGGL(delta_w_out, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->u, c->ld_v,
+                       (int64_t)c->d, c->K, solver, (float)(1.0 / (double)c->K), c->tmp_a);
     HIP_TRY(c, hipGetLastError());
-    HIP_TRY(c, hipMemcpyAsync(dw_out, c->dw_tmp, sizeof(float) * (size_t)c->d, hipMemcpyDeviceToHost, c->stream));
-    return check_deferred(c);
+    return read_vector(c, c->tmp_a, 1.0f, dw_out);
 }
 
 int chicle_get_alpha(chicle_ctx *c, int32_t chunk_id, float *alpha_out)
@@ -695,13 +841,6 @@ int chicle_get_assignment(chicle_ctx *c, int32_t *chunk_to_solver_out, int32_t *
     return CHICLE_OK;
 }
 
-int chicle_w_device(chicle_ctx *c, const float **w_device_out)
-{
-    if (!c || !w_device_out) return CHICLE_EINVAL;
-    *w_device_out = c->w;
-    return CHICLE_OK;
-}
-
 int chicle_sync(chicle_ctx *c)
 {
     if (!c) return CHICLE_EINVAL;
@@ -722,6 +861,23 @@ int chicle_last_kernel_ms(chicle_ctx *c, int32_t segment, float *ms_out)
     HIP_TRY(c, hipEventSynchronize(c->seg[segment].stop));
     HIP_TRY(c, hipEventElapsedTime(ms_out, c->seg[segment].start, c->seg[segment].stop));
     return CHICLE_OK;
+}
+
+int chicle_debug_gram(chicle_ctx *c, const int32_t *perm_device, float *tiles_out, int64_t capacity_floats,
+                      int32_t *n_tiles_out)
+{
+    if (!c || !perm_device) return CHICLE_EINVAL;
+    if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, "needs an assignment and no pending epoch");
+    if (!batched_eligible(c)) return fail(c, CHICLE_EINVAL, "batched solver not available for this data");
+    if (n_tiles_out) *n_tiles_out = c->n_tiles;
+    const int rc = c->loss == CHICLE_LOSS_HINGE ? launch_gram<0>(c, perm_device) : launch_gram<1>(c, perm_device);
+    if (rc) return rc;
+    if (tiles_out) {
+        const int64_t want = (int64_t)c->n_tiles * TILE_FLOATS;
+        if (capacity_floats < want) return fail(c, CHICLE_EINVAL, "need room for %lld floats", (long long)want);
+        HIP_TRY(c, hipMemcpyAsync(tiles_out, c->tiles, sizeof(float) * (size_t)want, hipMemcpyDeviceToHost, c->stream));
+    }
+    return check_deferred(c);
 }
 
 const char *chicle_last_error(chicle_ctx *c) { return c ? c->err.c_str() : "null context"; }

@@ -13,6 +13,7 @@ struct ChunkDev {
     const float *y;           // labels / targets
     float *alpha;             // dual variables (the per-sample state)
     const float *q;           // squared row norms
+    float *zw;                // x_i . w at the current shared vector (refreshed by the gap pass)
     int32_t n_rows;
     int32_t pad_;
     int64_t nnz;              // stored entries
@@ -24,7 +25,7 @@ struct SolverDev {
     int32_t list_begin;       // first entry of this solver in solver_chunks[] / solver_prefix[]
     int32_t n_chunks;
     int32_t n_rows;
-    int32_t pad_;
+    int32_t tile_begin;       // first Gram tile of this solver (batched solver); batches = ceil(n_rows/64)
 };
 
 // Scalars of one round.

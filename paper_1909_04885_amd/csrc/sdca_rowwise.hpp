@@ -2,11 +2,14 @@
 //
 // One workgroup per solver.  Every step is: row dot product against the solver's private vector
 // (workgroup reduction), closed-form dual step, alpha update inside the chunk, scatter of the row
-// into the private vector.  The private vector is v_k = w + sigma * Delta w_k, which turns the CoCoA
-// subproblem step into a plain coordinate step against v_k:
-//     hinge   : a' = clip(a + c (1 - y z) / q, 0, 1),  c = lambda n / sigma
+// into the private vector.  With v_k = w + sigma * Delta w_k the CoCoA subproblem step is a plain
+// coordinate step against v_k:
+//     hinge   : a' = clip(a + c (1 - y z) / q, 0, 1),  c = lambda n / sigma,  z = x_i . v_k
 //     squared : delta = (y - z - a) / (1 + q / c)
 //     v_k += (delta s / c) x_i,  s = y (hinge) or 1 (squared).
+// The private vector is stored as its difference u_k = v_k - w (zero when the pass starts), and
+// x_i . w comes from the per-row array zw that the gap pass left in the chunk, so z = zw_i + x_i . u_k.
+// Keeping the small difference apart from w keeps fp32 rounding relative to the update, not to w.
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
@@ -63,7 +66,7 @@ template <int LOSS, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
-    const int32_t *__restrict__ perm, float *v_all, int64_t ld_v, RoundScalars sc, int *err)
+    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, RoundScalars sc, int *err)
 {
     extern __shared__ int lists[];
     __shared__ float red[BLOCK / 64];
@@ -75,7 +78,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
     __syncthreads();
-    float *v = v_all + (int64_t)blockIdx.x * ld_v;
+    float *v = u_all + (int64_t)blockIdx.x * ld_v;
     const int32_t *pk = perm + S.perm_off;
     const int tid = threadIdx.x;
 
@@ -93,11 +96,12 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
         const float y = ch.y[r];
         const float a = ch.alpha[r];
+        const float zw = ch.zw[r];
         const int32_t *col = ch.col;
         const float *val = ch.val;
         float part = 0.0f;
         for (int p = b + tid; p < e; p += BLOCK) part += val[p] * v[col[p]];
-        const float z = block_sum<BLOCK>(part, red);
+        const float z = zw + block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
         if (tid == 0) ch.alpha[r] = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
@@ -113,7 +117,7 @@ template <int LOSS, int BLOCK, bool V_LDS>
 __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
-    const int32_t *__restrict__ perm, float *v_all, int64_t ld_v, int d, int max_list,
+    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, int d, int max_list,
     RoundScalars sc, int *err)
 {
     extern __shared__ int lists[];
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
     int *l_chunk = lists;
     int *l_prefix = lists + max_list;
     float *v_lds = reinterpret_cast<float *>(lists + 2 * max_list);
-    float *v_glb = v_all + (int64_t)blockIdx.x * ld_v;
+    float *v_glb = u_all + (int64_t)blockIdx.x * ld_v;
     const int tid = threadIdx.x;
     for (int i = tid; i < S.n_chunks; i += BLOCK) {
         l_chunk[i] = solver_chunks[S.list_begin + i];
@@ -148,9 +152,10 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
         const float *x = ch.val + (int64_t)r * d;
         const float y = ch.y[r];
         const float a = ch.alpha[r];
+        const float zw = ch.zw[r];
         float part = 0.0f;
         for (int p = tid; p < d; p += BLOCK) part += x[p] * v[p];
-        const float z = block_sum<BLOCK>(part, red);
+        const float z = zw + block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
         if (tid == 0) ch.alpha[r] = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;

@@ -26,8 +26,12 @@ def mods(oracle_mod):
     return oracle_mod, binding
 
 
-@pytest.mark.parametrize("name", ["dense_hinge", "dense_ridge", "sparse_zipf", "sparse_longrow", "elastic"])
-@pytest.mark.parametrize("solver", ["rowwise"])
+MINI_CASES = [("dense_hinge", "rowwise"), ("dense_ridge", "rowwise"), ("sparse_zipf", "rowwise"),
+              ("sparse_longrow", "rowwise"), ("elastic", "rowwise"), ("sparse_zipf", "batched"),
+              ("elastic", "batched")]
+
+
+@pytest.mark.parametrize("name,solver", MINI_CASES)
 def test_mini_all_solvers_every_round(mods, name, solver):
     oracle_mod, binding = mods
     cfg, p = cached_problem(name, "mini")
@@ -57,6 +61,45 @@ def test_full_sparse_longrow(mods):
     cfg, p = cached_problem("sparse_longrow", "full")
     print("\ncase sparse_longrow full n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
     run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 17, 63], log=_log)
+
+
+def test_gram_tiles_match_their_definition(mods):
+    """The batched solver's Gram kernel against x_i . x_j computed with numpy in double."""
+    import scipy.sparse as sp
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "mini")
+    K = 3
+    g = binding.ChicleRound.from_problem(p, max_solvers=K)
+    table = binding.balance(p.chunk_nnz(), K)
+    g.assign(K, table)
+    rows = g.solver_rows()
+    perms = round_permutations(3, 0, rows)
+    tiles = g.debug_gram(g.upload_perm(perms))
+    X = sp.csr_matrix((p.val.astype(np.float64), p.col, p.row_ptr), shape=(p.n, p.d))
+    q = np.asarray(X.multiply(X).sum(axis=1)).ravel()
+    y = p.y.astype(np.float64)
+    t = 0
+    for k in range(K):
+        own = np.concatenate([np.arange(*p.chunk_rows(c)) for c in np.nonzero(table == k)[0]])
+        order = own[perms[k]]
+        nb = (order.size + 63) // 64
+        for b in range(nb):
+            cur = order[b * 64:(b + 1) * 64]
+            prev = order[(b - 1) * 64:b * 64] if b > 0 else np.empty(0, dtype=np.int64)
+            want = np.zeros((128, 64))
+            Xc = X[cur]
+            if prev.size:
+                G = (X[prev] @ Xc.T).toarray()                      # [prev j, cur i]
+                want[:prev.size, :cur.size] = -G * y[prev][:, None] * y[cur][None, :] / q[cur][None, :]
+            G = (Xc @ Xc.T).toarray()
+            T = -G * y[cur][:, None] * y[cur][None, :] / q[cur][None, :]
+            T = np.triu(T, k=1)                                     # keep [j, i] with j < i
+            want[64:64 + cur.size, :cur.size] = T
+            got = tiles[t]
+            assert np.max(np.abs(got - want)) <= 2e-6 * max(1.0, np.max(np.abs(want))), (k, b)
+            t += 1
+    assert t == tiles.shape[0]
+    g.close()
 
 
 # ----------------------------------------------------------------------------- edges and contract
