@@ -105,8 +105,8 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
         if (live && sub == 0) {
-            ch.zw[r] = z;
-            const float y = ch.y[r], a = ch.alpha[r];
+            const float y = ch.st[r].y, a = ch.st[r].alpha;
+            ch.st[r].zw = z;
             if (LOSS == 0) {
                 s_loss += (double)fmaxf(0.f, 1.f - y * z);
                 s_conj += (double)(-a);
@@ -145,8 +145,8 @@ __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
         if (live && sub == 0) {
-            ch.zw[r] = z;
-            const float y = ch.y[r], a = ch.alpha[r];
+            const float y = ch.st[r].y, a = ch.st[r].alpha;
+            ch.st[r].zw = z;
             if (LOSS == 0) {
                 s_loss += (double)fmaxf(0.f, 1.f - y * z);
                 s_conj += (double)(-a);

@@ -30,6 +30,7 @@ constexpr int MAX_LIST_LDS = 4096;     // chunks one solver may own (its lists a
 constexpr int DENSE_V_LDS_MAX_D = 8192;
 constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
+constexpr int ENTRY_SLACK = 64;        // readable entries past the last row of a chunk
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
 
@@ -151,10 +152,10 @@ size_t chunk_bytes(bool dense, int64_t n_rows, int64_t entries)
     size_t s = 0;
     if (!dense) {
         s += align_up(sizeof(int32_t) * (size_t)(n_rows + 1));
-        s += align_up(sizeof(int32_t) * (size_t)std::max<int64_t>(entries, 1));
+        s += align_up(sizeof(int32_t) * (size_t)(entries + ENTRY_SLACK));
     }
-    s += align_up(sizeof(float) * (size_t)std::max<int64_t>(entries, 1));
-    s += 4 * align_up(sizeof(float) * (size_t)n_rows);
+    s += align_up(sizeof(float) * (size_t)(entries + ENTRY_SLACK));
+    s += align_up(sizeof(RowState) * (size_t)n_rows);
     return s;
 }
 
@@ -270,12 +271,13 @@ int launch_batched(chicle_ctx *c, const int32_t *perm)
     seg_end(c, CHICLE_SEG_EPOCH_GRAM);
     if (rc) return rc;
     const int ml = std::max(c->max_list, 1);
-    const size_t sh = sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml;
+    const int n_hot = (int)std::min<int64_t>(HOT_COLS, c->d);
+    const size_t sh = sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + sizeof(float) * (size_t)n_hot;
     auto kern = sdca_batched_csr<LOSS>;
     HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
     seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
     hipLaunchKernelGGL(kern, dim3(c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
-                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles, c->u, c->ld_v, ml, sc,
+                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles, c->u, c->ld_v, ml, n_hot, sc,
                        c->err_dev);
     seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
     HIP_TRY(c, hipGetLastError());
@@ -381,7 +383,7 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
     if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
     size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
-    const size_t per_chunk_slack = 8 * ALIGN;
+    const size_t per_chunk_slack = 8 * ALIGN + 2 * sizeof(float) * ENTRY_SLACK;
     if (dense)
         s += sizeof(float) * (size_t)total_entries + 4 * sizeof(float) * (size_t)n_total;
     else
@@ -482,18 +484,15 @@ static int check_state_arrays(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, c
 static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const float *y, const float *alpha0,
                        const std::vector<float> &q)
 {
-    const size_t nb = sizeof(float) * (size_t)ch.n_rows;
-    float *yd = (float *)carve(c, nb);
-    float *ad = (float *)carve(c, nb);
-    float *qd = (float *)carve(c, nb);
-    float *zd = (float *)carve(c, nb);
-    if (!zd) return fail(c, CHICLE_ENOMEM, "chunk store full");
-    ch.y = yd; ch.alpha = ad; ch.q = qd; ch.zw = zd;
-    HIP_TRY(c, hipMemcpyAsync(yd, y, nb, hipMemcpyHostToDevice, c->stream));
-    if (alpha0) HIP_TRY(c, hipMemcpyAsync(ad, alpha0, nb, hipMemcpyHostToDevice, c->stream));
-    else HIP_TRY(c, hipMemsetAsync(ad, 0, nb, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(qd, q.data(), nb, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, hipMemsetAsync(zd, 0, nb, c->stream));
+    const size_t nb = sizeof(RowState) * (size_t)ch.n_rows;
+    RowState *sd = (RowState *)carve(c, nb);
+    if (!sd) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    ch.st = sd;
+    std::vector<RowState> st(ch.n_rows);
+    for (int32_t r = 0; r < ch.n_rows; ++r) {
+        st[r].y = y[r]; st[r].alpha = alpha0 ? alpha0[r] : 0.f; st[r].q = q[r]; st[r].zw = 0.f;
+    }
+    HIP_TRY(c, hipMemcpyAsync(sd, st.data(), nb, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));   // host arrays are the caller's again on return
     c->chunks[chunk_id] = ch;
     c->loaded[chunk_id] = 1;
@@ -534,8 +533,9 @@ int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const
     ChunkDev ch{};
     ch.n_rows = n_rows; ch.nnz = nnz;
     int32_t *rp = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(n_rows + 1));
-    int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1));
-    float *vd = (float *)carve(c, sizeof(float) * (size_t)std::max<int64_t>(nnz, 1));
+    // a few entries of slack: kernels read short rows with fixed-width vector loads
+    int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
+    float *vd = (float *)carve(c, sizeof(float) * (size_t)(nnz + ENTRY_SLACK));
     if (!vd) return fail(c, CHICLE_ENOMEM, "chunk store full");
     ch.row_ptr = rp; ch.col = cd; ch.val = vd;
     HIP_TRY(c, hipMemcpyAsync(rp, row_ptr, sizeof(int32_t) * (size_t)(n_rows + 1), hipMemcpyHostToDevice, c->stream));
@@ -812,7 +812,8 @@ int chicle_get_alpha(chicle_ctx *c, int32_t chunk_id, float *alpha_out)
     if (!c || !alpha_out) return CHICLE_EINVAL;
     if (chunk_id < 0 || chunk_id >= c->n_chunks || !c->loaded[chunk_id]) return fail(c, CHICLE_EINVAL, "chunk %d not loaded", chunk_id);
     const ChunkDev &ch = c->chunks[chunk_id];
-    HIP_TRY(c, hipMemcpyAsync(alpha_out, ch.alpha, sizeof(float) * (size_t)ch.n_rows, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpy2DAsync(alpha_out, sizeof(float), &ch.st->alpha, sizeof(RowState), sizeof(float),
+                                (size_t)ch.n_rows, hipMemcpyDeviceToHost, c->stream));
     return check_deferred(c);
 }
 
@@ -827,7 +828,8 @@ int chicle_set_alpha(chicle_ctx *c, int32_t chunk_id, const float *alpha_in)
         if (c->loss == CHICLE_LOSS_HINGE && (alpha_in[r] < 0.f || alpha_in[r] > 1.f))
             return fail(c, CHICLE_EINVAL, "hinge alpha outside [0,1] at row %d", r);
     }
-    HIP_TRY(c, hipMemcpyAsync(ch.alpha, alpha_in, sizeof(float) * (size_t)ch.n_rows, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpy2DAsync(&ch.st->alpha, sizeof(RowState), alpha_in, sizeof(float), sizeof(float),
+                                (size_t)ch.n_rows, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return CHICLE_OK;
 }

@@ -4,16 +4,22 @@
 
 namespace chicle {
 
+// Per-sample state that travels with its row (paper Section 4.4).  One record per row so that a
+// randomly visited row costs one 16-byte access.
+struct RowState {
+    float y;        // label / target
+    float alpha;    // dual variable
+    float q;        // squared row norm
+    float zw;       // x_i . w at the current shared vector (refreshed by the gap pass)
+};
+
 // One data chunk as the kernels see it (paper Section 4.4: sparse or dense rows plus per-sample
 // state in one contiguous block; all pointers point into that block).
 struct ChunkDev {
     const int32_t *row_ptr;   // CSR: n_rows + 1 chunk-local offsets; dense: nullptr
     const int32_t *col;       // CSR column ids; dense: nullptr
     const float *val;         // CSR values, or dense row-major n_rows x d
-    const float *y;           // labels / targets
-    float *alpha;             // dual variables (the per-sample state)
-    const float *q;           // squared row norms
-    float *zw;                // x_i . w at the current shared vector (refreshed by the gap pass)
+    RowState *st;             // per-row state, one 16-byte record per row
     int32_t n_rows;
     int32_t pad_;
     int64_t nnz;              // stored entries

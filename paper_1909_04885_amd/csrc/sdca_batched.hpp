@@ -27,27 +27,45 @@ constexpr int TILE_W = 2 * BATCH;            // T rows: previous block (cross pa
 constexpr int TILE_FLOATS = BATCH * TILE_W;  // layout [jp][i]: jp in [0,128), i in [0,64)
 constexpr int GRAM_MAX_ROW = 48;             // longest sparse row the batched solver accepts
 constexpr int LPR = 8;                       // helper lanes per row
-constexpr int ENT = GRAM_MAX_ROW / LPR;      // entries per helper lane
+constexpr int ENT = GRAM_MAX_ROW / LPR;      // entries per helper lane (6: one 16-byte and one 8-byte load)
 constexpr int HELPER_WAVES = BATCH * LPR / 64;
 constexpr int BATCHED_THREADS = 64 + BATCH * LPR;
 constexpr int RING = 8;
+constexpr int HOT_COLS = 12288;               // head of the private vector kept in LDS (popular columns)
+
+// Loads and stores through pointers that were parked in LDS: the compiler no longer knows that they
+// point to HBM and would emit flat accesses, whose completion is counted together with LDS traffic.
+#define CHICLE_GLOBAL __attribute__((address_space(1)))
+typedef int int2_a4 __attribute__((ext_vector_type(2), aligned(4)));
+typedef int int4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef float float2_a4 __attribute__((ext_vector_type(2), aligned(4)));
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ int gld(const int32_t *p) { return *(const CHICLE_GLOBAL int32_t *)p; }
+__device__ __forceinline__ float gld(const float *p) { return *(const CHICLE_GLOBAL float *)p; }
+__device__ __forceinline__ int2_a4 gld2(const int32_t *p) { return *(const CHICLE_GLOBAL int2_a4 *)p; }
+__device__ __forceinline__ int4_a4 gld4(const int32_t *p) { return *(const CHICLE_GLOBAL int4_a4 *)p; }
+__device__ __forceinline__ float2_a4 gld2(const float *p) { return *(const CHICLE_GLOBAL float2_a4 *)p; }
+__device__ __forceinline__ float4_a4 gld4(const float *p) { return *(const CHICLE_GLOBAL float4_a4 *)p; }
+typedef float float4_v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4_v gld_state(const RowState *p) { return *(const CHICLE_GLOBAL float4_v *)p; }
+__device__ __forceinline__ void gst(float *p, float x) { *(CHICLE_GLOBAL float *)p = x; }
 
 // What the helpers know about one row of a block.
 struct RowSlot {
-    const int32_t *col;
+    const int32_t *col;   // always readable for ENT * LPR entries (a dummy row when len = 0)
     const float *val;
-    float *alpha_p;
-    int len;          // 0 for a missing, empty or rejected row
+    RowState *st;
+    int len;              // 0 for a missing, empty or rejected row
     float y, alpha, q, zw;
 };
 
-// Resolve local row lr of a solver (lists in LDS or global) into a RowSlot; len = 0 if unusable.
+// Resolve local row lr of a solver (lists in global memory) into a RowSlot; len = 0 if unusable.
 __device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunks, const int *l_chunk,
                                               const int *l_prefix, int n_list, int n_rows, int lr,
                                               int *err)
 {
     RowSlot s;
-    s.col = nullptr; s.val = nullptr; s.alpha_p = nullptr; s.len = 0;
+    s.col = nullptr; s.val = nullptr; s.st = nullptr; s.len = 0;
     s.y = 0.f; s.alpha = 0.f; s.q = 0.f; s.zw = 0.f;
     if (lr < 0) return s;
     if (lr >= n_rows) { atomicOr(err, ERR_PERM_RANGE); return s; }
@@ -55,10 +73,11 @@ __device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunk
     const ChunkDev &ch = chunks[l_chunk[j]];
     const int r = lr - l_prefix[j];
     const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-    s.q = ch.q[r];
+    const RowState st = ch.st[r];
+    s.q = st.q;
     if (s.q == 0.f || e - b > GRAM_MAX_ROW) return s;
-    s.col = ch.col + b; s.val = ch.val + b; s.alpha_p = ch.alpha + r; s.len = e - b;
-    s.y = ch.y[r]; s.alpha = ch.alpha[r]; s.zw = ch.zw[r];
+    s.col = ch.col + b; s.val = ch.val + b; s.st = ch.st + r; s.len = e - b;
+    s.y = st.y; s.alpha = st.alpha; s.zw = st.zw;
     return s;
 }
 
@@ -167,13 +186,13 @@ __device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, 
 }
 
 // One workgroup per solver: wavefront 0 runs the chain, the others gather, scatter and stage.
-// Dynamic LDS: BatchedShared, then max_list chunk descriptors and max_list local-row prefixes.
+// Dynamic LDS: BatchedShared, then max_list chunk descriptors, max_list local-row prefixes, n_hot floats.
 template <int LOSS>
 __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
     const int32_t *__restrict__ perm, const float *__restrict__ tiles, float *u_all, int64_t ld_v,
-    int max_list, RoundScalars sc, int *err)
+    int max_list, int n_hot, RoundScalars sc, int *err)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     BatchedShared &sh = *reinterpret_cast<BatchedShared *>(smem);
@@ -185,6 +204,9 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
+    // columns [0, n_hot) of the private vector live here for the whole pass (it starts at zero)
+    float *hot = reinterpret_cast<float *>(l_prefix + max_list);
+    for (int i = tid; i < n_hot; i += BATCHED_THREADS) hot[i] = 0.f;
     if (tid == 0) sh.hb = 0;
     __syncthreads();
     float *u = u_all + (int64_t)blockIdx.x * ld_v;
@@ -197,75 +219,76 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const int hl = tid - 64, rho = hl >> 3, sub = hl & (LPR - 1);
 
     // helper pipeline registers
-    int p_cur = -1, p_next = -1;                 // visiting-order entries (sub == 0 lanes)
-    int m_ci = -1, m_r = 0, m_rp0 = 0, m_rp1 = 0;   // row being resolved: loads in flight
-    float m_q = 0.f, m_y = 0.f, m_a = 0.f, m_zw = 0.f;
-    int g_col[ENT], s_col[ENT], gn_col[ENT], sn_col[ENT];
-    float g_val[ENT], s_val[ENT], gn_val[ENT], sn_val[ENT];
+    int p_cur = -1, p_next = -1;                     // visiting-order entries (meta lanes: hl < 64)
+    int m_ci = -1, m_r = 0;                          // row being resolved: loads in flight
+    int2_a4 m_rp = {0, 0};
+    float4_v m_st = {0.f, 0.f, 0.f, 0.f};          // kept whole until it is used (y, alpha, q, zw)
+    // Entries of a row segment (ENT consecutive entries per lane) travel through four stages:
+    // in (loads in flight) -> g (gathered this iteration) -> c (its block is in the chain) -> s (scattered).
+    int in_c[ENT], g_c[ENT], c_c[ENT], s_c[ENT];
+    float in_v[ENT], g_v[ENT], c_v[ENT], s_v[ENT];
 #pragma unroll
     for (int e = 0; e < ENT; ++e) {
-        g_col[e] = s_col[e] = gn_col[e] = sn_col[e] = 0;
-        g_val[e] = s_val[e] = gn_val[e] = sn_val[e] = 0.f;
+        in_c[e] = g_c[e] = c_c[e] = s_c[e] = 0;
+        in_v[e] = g_v[e] = c_v[e] = s_v[e] = 0.f;
     }
+    int in_len = 0;
     float x_carry = 0.f;
     int hb_target = 0;
+    if (nb == 0) return;                             // a solver without rows (uniform for the workgroup)
+    const bool meta = !is_chain && hl < BATCH;       // one helper wavefront resolves the 64 rows of a block
 
     for (int i = -5; i <= nb; ++i) {
         if (is_chain) {
             if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry);
         } else {
             // 1. publish the row of block i + 3 whose state loads were issued last iteration
-            if (sub == 0 && i + 3 >= 0 && i + 3 < nb) {
+            if (meta && i + 3 >= 0 && i + 3 < nb) {
                 RowSlot s;
-                s.col = nullptr; s.val = nullptr; s.alpha_p = nullptr; s.len = 0;
-                s.y = m_y; s.alpha = m_a; s.q = m_q; s.zw = m_zw;
-                const int len = m_rp1 - m_rp0;
-                if (m_ci >= 0 && m_q != 0.f && len > 0 && len <= GRAM_MAX_ROW) {
+                s.col = l_desc[0].col; s.val = l_desc[0].val; s.st = nullptr; s.len = 0;
+                s.y = m_st.x; s.alpha = m_st.y; s.q = m_st.z; s.zw = m_st.w;
+                const int len = m_rp.y - m_rp.x;
+                if (m_ci >= 0 && s.q != 0.f && len > 0 && len <= GRAM_MAX_ROW) {
                     const ChunkDev &ch = l_desc[m_ci];
-                    s.col = ch.col + m_rp0; s.val = ch.val + m_rp0; s.alpha_p = ch.alpha + m_r;
+                    s.col = ch.col + m_rp.x; s.val = ch.val + m_rp.x; s.st = ch.st + m_r;
                     s.len = len;
                 }
-                sh.rows[(i + 3) & (RING - 1)][rho] = s;
+                sh.rows[(i + 3) & (RING - 1)][hl] = s;
             }
             // 2. issue the state loads of block i + 4 from the order entry read last iteration
             m_ci = -1;
-            if (sub == 0 && i + 4 >= 0 && i + 4 < nb && p_cur >= 0) {
+            if (meta && i + 4 >= 0 && i + 4 < nb && p_cur >= 0) {
                 if (p_cur >= S.n_rows) {
                     atomicOr(err, ERR_PERM_RANGE);
                 } else {
                     m_ci = find_chunk(l_prefix, S.n_chunks, p_cur);
                     m_r = p_cur - l_prefix[m_ci];
                     const ChunkDev &ch = l_desc[m_ci];
-                    m_rp0 = ch.row_ptr[m_r]; m_rp1 = ch.row_ptr[m_r + 1];
-                    m_q = ch.q[m_r]; m_y = ch.y[m_r]; m_a = ch.alpha[m_r]; m_zw = ch.zw[m_r];
+                    m_rp = gld2(ch.row_ptr + m_r);
+                    m_st = gld_state(ch.st + m_r);
                 }
             }
             // 3. read the order entry of block i + 5
             p_next = -1;
-            if (sub == 0 && i + 5 >= 0 && i + 5 < nb) {
-                const int t = (i + 5) * BATCH + rho;
+            if (meta && i + 5 >= 0 && i + 5 < nb) {
+                const int t = (i + 5) * BATCH + hl;
                 if (t < S.n_rows) p_next = pk[t];
             }
-            // 4. fetch the entries of block i + 2 (for its gather) and of block i (for its scatter)
-#pragma unroll
-            for (int e = 0; e < ENT; ++e) { gn_col[e] = 0; gn_val[e] = 0.f; sn_col[e] = 0; sn_val[e] = 0.f; }
+            // 4. fetch this lane's segment of the row of block i + 2 (unconditional vector loads; the
+            //    entries beyond the row's length are masked when the set moves on)
             if (i + 2 >= 0 && i + 2 < nb) {
                 const RowSlot &r = sh.rows[(i + 2) & (RING - 1)][rho];
-                const int len = r.len;
-#pragma unroll
-                for (int e = 0; e < ENT; ++e) {
-                    const int p = sub + e * LPR;
-                    if (p < len) { gn_col[e] = r.col[p]; gn_val[e] = r.val[p]; }
-                }
-            }
-            if (i >= 0 && i < nb) {
-                const RowSlot &r = sh.rows[i & (RING - 1)][rho];
-                const int len = r.len;
-#pragma unroll
-                for (int e = 0; e < ENT; ++e) {
-                    const int p = sub + e * LPR;
-                    if (p < len) { sn_col[e] = r.col[p]; sn_val[e] = r.val[p]; }
-                }
+                const int32_t *cp = r.col + sub * ENT;
+                const float *vp = r.val + sub * ENT;
+                in_len = r.len;
+                const int4_a4 c4 = gld4(cp);
+                const int2_a4 c2 = gld2(cp + 4);
+                const float4_a4 v4 = gld4(vp);
+                const float2_a4 v2 = gld2(vp + 4);
+                in_c[0] = c4.x; in_c[1] = c4.y; in_c[2] = c4.z; in_c[3] = c4.w; in_c[4] = c2.x; in_c[5] = c2.y;
+                in_v[0] = v4.x; in_v[1] = v4.y; in_v[2] = v4.z; in_v[3] = v4.w; in_v[4] = v2.x; in_v[5] = v2.y;
+            } else {
+                in_len = 0;
             }
             // tile staging loads for iteration i + 1: own part of T(i+1), cross part of T(i+2)
             float4 tw_a = make_float4(0.f, 0.f, 0.f, 0.f), tw_b = tw_a, tx_a = tw_a, tx_b = tw_a;
@@ -278,7 +301,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 const float4 *src = reinterpret_cast<const float4 *>(my_tiles + (int64_t)(i + 2) * TILE_FLOATS);
                 tx_a = src[hl]; tx_b = src[hl + 512];
             }
-            // 5. scatter block i - 1: alpha and the private vector
+            // 5. scatter block i - 1: alpha and the private vector (masked entries carry value 0)
             if (i - 1 >= 0 && i - 1 < nb) {
                 const RowSlot &r = sh.rows[(i - 1) & (RING - 1)][rho];
                 const float dl = sh.delta[(i - 1) & 1][rho];
@@ -286,11 +309,14 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                     const float coef = dl * (LOSS == 0 ? r.y : 1.f) * sc.inv_c;
 #pragma unroll
                     for (int e = 0; e < ENT; ++e)
-                        if (sub + e * LPR < r.len) unsafeAtomicAdd(&u[s_col[e]], coef * s_val[e]);
+                        if (s_v[e] != 0.f) {
+                            if (s_c[e] < n_hot) atomicAdd(&hot[s_c[e]], coef * s_v[e]);
+                            else unsafeAtomicAdd(&u[s_c[e]], coef * s_v[e]);
+                        }
                     if (sub == 0) {
                         float an = r.alpha + dl;
                         if (LOSS == 0) an = fminf(fmaxf(an, 0.f), 1.f);
-                        *r.alpha_p = an;
+                        gst(&r.st->alpha, an);
                     }
                 }
             }
@@ -300,11 +326,19 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
             // 7. gather block i + 1 against the private vector (blocks <= i - 1 applied)
             if (i + 1 >= 0 && i + 1 < nb) {
                 const RowSlot &r = sh.rows[(i + 1) & (RING - 1)][rho];
+                // Unconditional loads (masked entries hold column 0 with value 0), all issued before
+                // the first use, so that one round trip covers the whole gather.
+                float cold_v[ENT], hot_v[ENT];
+#pragma unroll
+                for (int e = 0; e < ENT; ++e) {
+                    const bool cold = g_c[e] >= n_hot;
+                    cold_v[e] = __hip_atomic_load(u + (cold ? g_c[e] : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    hot_v[e] = hot[cold ? 0 : g_c[e]];
+                }
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < ENT; ++e)
-                    if (sub + e * LPR < r.len)
-                        part += g_val[e] * __hip_atomic_load(&u[g_col[e]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    part += g_v[e] * (g_c[e] >= n_hot ? cold_v[e] : hot_v[e]);
                 part += __shfl_xor(part, 1, 64);
                 part += __shfl_xor(part, 2, 64);
                 part += __shfl_xor(part, 4, 64);
@@ -331,16 +365,20 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 dw[hl] = tw_a; dw[hl + 512] = tw_b;
                 dx[hl] = tx_a; dx[hl + 512] = tx_b;
             }
-            // 9. rotate the pipeline registers
+            // 9. move the entry sets one stage on; the incoming set is masked to the row's length
 #pragma unroll
             for (int e = 0; e < ENT; ++e) {
-                g_col[e] = gn_col[e]; g_val[e] = gn_val[e];
-                s_col[e] = sn_col[e]; s_val[e] = sn_val[e];
+                s_c[e] = c_c[e]; s_v[e] = c_v[e];
+                c_c[e] = g_c[e]; c_v[e] = g_v[e];
+                const bool live = sub * ENT + e < in_len;
+                g_c[e] = live ? in_c[e] : 0;
+                g_v[e] = live ? in_v[e] : 0.f;
             }
             p_cur = p_next;
         }
         __syncthreads();
     }
+    for (int i = tid; i < n_hot; i += BATCHED_THREADS) u[i] = hot[i];
 }
 
 }  // namespace chicle

@@ -91,19 +91,20 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         const int j = find_chunk(l_prefix, S.n_chunks, lr);
         const ChunkDev &ch = chunks[l_chunk[j]];
         const int r = lr - l_prefix[j];
-        const float q = ch.q[r];
+        const RowState st = ch.st[r];
+        const float q = st.q;
         if (q == 0.0f) continue;
         const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-        const float y = ch.y[r];
-        const float a = ch.alpha[r];
-        const float zw = ch.zw[r];
+        const float y = st.y;
+        const float a = st.alpha;
+        const float zw = st.zw;
         const int32_t *col = ch.col;
         const float *val = ch.val;
         float part = 0.0f;
         for (int p = b + tid; p < e; p += BLOCK) part += val[p] * v[col[p]];
         const float z = zw + block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
-        if (tid == 0) ch.alpha[r] = a + delta;
+        if (tid == 0) ch.st[r].alpha = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
         if (coef != 0.0f)
             for (int p = b + tid; p < e; p += BLOCK) v[col[p]] += coef * val[p];
@@ -147,17 +148,18 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
         const int j = find_chunk(l_prefix, S.n_chunks, lr);
         const ChunkDev &ch = chunks[l_chunk[j]];
         const int r = lr - l_prefix[j];
-        const float q = ch.q[r];
+        const RowState st = ch.st[r];
+        const float q = st.q;
         if (q == 0.0f) continue;
         const float *x = ch.val + (int64_t)r * d;
-        const float y = ch.y[r];
-        const float a = ch.alpha[r];
-        const float zw = ch.zw[r];
+        const float y = st.y;
+        const float a = st.alpha;
+        const float zw = st.zw;
         float part = 0.0f;
         for (int p = tid; p < d; p += BLOCK) part += x[p] * v[p];
         const float z = zw + block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
-        if (tid == 0) ch.alpha[r] = a + delta;
+        if (tid == 0) ch.st[r].alpha = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
         if (coef != 0.0f)
             for (int p = tid; p < d; p += BLOCK) v[p] += coef * x[p];
