@@ -15,6 +15,7 @@
 #include "../../include/chicle_round.h"
 #include "aggregate_gap.hpp"
 #include "device_types.hpp"
+#include "gram_join.hpp"
 #include "layout.hpp"
 #include "sdca_batched.hpp"
 #include "sdca_rowwise.hpp"
@@ -72,6 +73,7 @@ struct chicle_ctx {
     int32_t max_row_len = 0;
     float *tiles = nullptr;
     int32_t *tile_solver_dev = nullptr;
+    int32_t *row_chunk_dev = nullptr, *chunk_first_dev = nullptr, *list_base_dev = nullptr;
     int64_t max_tiles = 0;
     int32_t n_tiles = 0;
     bool zw_valid = true;      // zw = X w holds trivially for w = 0 after loading
@@ -140,7 +142,8 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
     s += align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
     s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
-    s += align_up(sizeof(int32_t) * (size_t)n_total);                    // perm staging
+    s += 2 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, row -> chunk
+    s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);               // chunk_first, list_base
     s += 2 * align_up(sizeof(double) * GAP_PARTS) + 2 * align_up(sizeof(double) * WSQ_PARTS);
     s += align_up(sizeof(double) * 4);
     s += align_up(sizeof(int));
@@ -254,10 +257,14 @@ template <int LOSS>
 int launch_gram(chicle_ctx *c, const int32_t *perm)
 {
     const RoundScalars sc = scalars(c);
-    if (c->n_tiles > 0)
-        hipLaunchKernelGGL((gram_tiles_merge<LOSS>), dim3(c->n_tiles), dim3(256), 0, c->stream, c->chunks_dev,
-                           c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm,
+    if (c->n_tiles > 0) {
+        auto kern = gram_tiles_join<LOSS>;
+        HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)sizeof(GramShared)));
+        hipLaunchKernelGGL(kern, dim3(c->n_tiles), dim3(GRAM_THREADS), sizeof(GramShared), c->stream,
+                           c->chunks_dev, c->solvers_dev, c->row_chunk_dev, c->chunk_first_dev, perm,
                            c->tile_solver_dev, c->tiles, sc.c, c->err_dev);
+    }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;
 }
@@ -428,6 +435,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->tiles = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
     c->tile_solver_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->max_tiles);
     c->perm_stage = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
+    c->row_chunk_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
+    c->chunk_first_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
+    c->list_base_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     c->part_loss = (double *)carve(c, sizeof(double) * GAP_PARTS);
     c->part_conj = (double *)carve(c, sizeof(double) * GAP_PARTS);
     c->part_wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
@@ -613,7 +623,7 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     if (max_list > MAX_LIST_LDS) return fail(c, CHICLE_EINVAL, "a solver owns %d chunks, limit %d", max_list, MAX_LIST_LDS);
 
     std::vector<SolverDev> sol(K);
-    std::vector<int32_t> list(c->n_chunks), prefix(c->n_chunks);
+    std::vector<int32_t> list(c->n_chunks), prefix(c->n_chunks), chunk_first(c->n_chunks), list_base(c->n_chunks);
     int32_t pos = 0, tile = 0;
     int64_t perm_off = 0;
     for (int32_t k = 0; k < K; ++k) {
@@ -621,7 +631,8 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
         int32_t rows = 0;
         for (int32_t i = 0; i < c->n_chunks; ++i) {        // ascending chunk id
             if (chunk_to_solver[i] != k) continue;
-            list[pos] = i; prefix[pos] = rows; rows += c->chunks[i].n_rows; ++pos;
+            list[pos] = i; prefix[pos] = rows; chunk_first[i] = rows; list_base[pos] = (int32_t)(perm_off + rows);
+            rows += c->chunks[i].n_rows; ++pos;
         }
         sol[k].n_rows = rows;
         sol[k].tile_begin = tile;
@@ -648,6 +659,11 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     HIP_TRY(c, hipMemcpyAsync(c->solver_prefix_dev, prefix.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->item_prefix_dev, items.data(), sizeof(int32_t) * ((size_t)c->n_chunks + 1), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->tile_solver_dev, tile_solver.data(), sizeof(int32_t) * (size_t)tile, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->chunk_first_dev, chunk_first.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->list_base_dev, list_base.data(), sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+    hipLaunchKernelGGL(fill_row_chunk, dim3(c->n_chunks), dim3(256), 0, c->stream, c->chunks_dev,
+                       c->solver_chunks_dev, c->list_base_dev, c->row_chunk_dev);
+    HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (c->state == ST_LOADING && !c->dense && c->max_row_len <= RENUMBER_MAX_ROW) {
         const int rc = renumber_columns(c);

@@ -82,64 +82,6 @@ __device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunk
 }
 
 // ------------------------------------------------------------------------------------------------
-// Gram blocks, reference form: every pair by a merge of the two sorted rows staged in LDS.
-// One workgroup per block.  tile_solver[tile] = solver that owns the tile.
-template <int LOSS>
-__global__ __launch_bounds__(256) void gram_tiles_merge(
-    const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
-    const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
-    const int32_t *__restrict__ perm, const int32_t *__restrict__ tile_solver, float *tiles, float c,
-    int *err)
-{
-    __shared__ int e_col[TILE_W * GRAM_MAX_ROW];
-    __shared__ float e_val[TILE_W * GRAM_MAX_ROW];
-    __shared__ int r_len[TILE_W];
-    __shared__ float r_sgn[TILE_W];
-    __shared__ float r_scale[BATCH];
-    const int tile = blockIdx.x;
-    const int k = tile_solver[tile];
-    const SolverDev S = solvers[k];
-    const int beta = tile - S.tile_begin;
-    const int tid = threadIdx.x;
-    if (tid < TILE_W) {
-        const int b = tid < BATCH ? beta - 1 : beta;
-        const int t = b * BATCH + (tid & (BATCH - 1));
-        int lr = -1;
-        if (b >= 0 && t < S.n_rows) lr = perm[S.perm_off + t];
-        const RowSlot s = locate_row(chunks, solver_chunks + S.list_begin, solver_prefix + S.list_begin,
-                                     S.n_chunks, S.n_rows, lr, err);
-        r_len[tid] = s.len;
-        r_sgn[tid] = LOSS == 0 ? s.y : 1.f;
-        for (int p = 0; p < s.len; ++p) {
-            e_col[tid * GRAM_MAX_ROW + p] = s.col[p];
-            e_val[tid * GRAM_MAX_ROW + p] = s.val[p];
-        }
-        if (tid >= BATCH)
-            r_scale[tid - BATCH] = s.len == 0 ? 0.f : (LOSS == 0 ? -1.f / s.q : -1.f / (c + s.q));
-    }
-    __syncthreads();
-    float *out = tiles + (int64_t)tile * TILE_FLOATS;
-    for (int idx = tid; idx < TILE_FLOATS; idx += 256) {
-        const int jp = idx >> 6, i = idx & 63;
-        float g = 0.f;
-        if (jp < BATCH || jp - BATCH < i) {
-            const int *ca = e_col + (BATCH + i) * GRAM_MAX_ROW, *cb = e_col + jp * GRAM_MAX_ROW;
-            const float *va = e_val + (BATCH + i) * GRAM_MAX_ROW, *vb = e_val + jp * GRAM_MAX_ROW;
-            const int la = r_len[BATCH + i], lb = r_len[jp];
-            int pa = 0, pb = 0;
-            while (pa < la && pb < lb) {
-                const int x = ca[pa], yv = cb[pb];
-                if (x == yv) { g += va[pa] * vb[pb]; ++pa; ++pb; }
-                else if (x < yv) ++pa;
-                else ++pb;
-            }
-            g *= r_scale[i] * r_sgn[BATCH + i] * r_sgn[jp];
-        }
-        out[idx] = g;
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
 // Workgroup-internal barrier among the helper wavefronts only (the chain wavefront keeps running).
 // cnt lives in LDS and only grows; target = arrivals expected so far.
 __device__ __forceinline__ void helper_barrier(int *cnt, int target)
