@@ -261,9 +261,11 @@ int launch_gram(chicle_ctx *c, const int32_t *perm)
         auto kern = gram_tiles_join<LOSS>;
         HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)sizeof(GramShared)));
-        hipLaunchKernelGGL(kern, dim3(c->n_tiles), dim3(GRAM_THREADS), sizeof(GramShared), c->stream,
+        // each workgroup takes a contiguous run of tiles (neighbouring tiles share half their rows)
+        const int grid = std::min(c->n_tiles, 2048);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(GRAM_THREADS), sizeof(GramShared), c->stream,
                            c->chunks_dev, c->solvers_dev, c->row_chunk_dev, c->chunk_first_dev, perm,
-                           c->tile_solver_dev, c->tiles, sc.c, c->err_dev);
+                           c->tile_solver_dev, c->tiles, c->n_tiles, sc.c, c->err_dev);
     }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;

@@ -1,14 +1,18 @@
-// Gram blocks of the batched solver, fast form.
+// Gram blocks of the batched solver.
 //
 // A tile couples the 64 rows of one block (i) with the 64 rows of the previous block and the earlier
 // rows of the same block (jp): T[jp][i] = scale_i s_i s_j (x_i . x_j).  Columns are stored as popularity
 // ranks, so a row's entries split by a range test:
 //   - popular columns (rank < GRAM_DENSE): the window's values go into a small dense matrix in LDS and
-//     their contribution is a register-tiled dense product (every row has most of these columns);
+//     their contribution is a register-tiled dense product (most rows have most of these columns);
 //   - all other columns: a hash join in LDS.  Entries are inserted into an open-addressing table keyed
-//     by column, counted per slot, laid out as posting lists by a scan, and every entry of a block row
-//     walks the (short) list of its column, adding its products with float atomics in LDS.
+//     by column, counted per slot, laid out as posting lists (row, value) by a scan, and every entry of
+//     a block row walks the short list of its column, adding its products with float atomics in LDS.
 // The summation order of the join is not fixed, so tiles can differ in the last bits between runs.
+//
+// Each workgroup owns a contiguous range of tiles and works through it; the row lookups of the next
+// tile (visiting order -> chunk -> row offsets, a chain of dependent loads) are spread over the phases
+// of the current tile so that their latency is hidden.
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
@@ -18,30 +22,44 @@ namespace chicle {
 
 constexpr int GRAM_DENSE = 32;                        // columns handled by the dense product
 constexpr int GRAM_THREADS = 1024;
-constexpr int GRAM_SLOTS = 8192;                      // hash slots (>= window entries / 0.75)
+constexpr int GRAM_SLOTS = 8192;                      // hash slots (> window entries, so probing ends)
 constexpr int GRAM_ENTRIES = TILE_W * GRAM_MAX_ROW;   // 6144 entry positions: row slot * 48 + p
+constexpr int GRAM_EPT = GRAM_ENTRIES / GRAM_THREADS; // entry positions per thread
 constexpr int G_LD = BATCH + 1;                       // padded row of the accumulator tile
+
+struct GramRows {                                     // the 128 rows of a window
+    const int32_t *col[TILE_W];
+    const float *val[TILE_W];
+    int len[TILE_W];
+    float sgn[TILE_W];
+    float scale[BATCH];
+};
 
 struct GramShared {
     float G[TILE_W][G_LD];                 // accumulators [jp][i]
     float A[GRAM_DENSE][TILE_W];           // dense part, [column][window row]
-    float e_val[GRAM_ENTRIES];             // values of the sparse-part entries
     int keys[GRAM_SLOTS];                  // column per slot during insertion, then fill cursors
-    unsigned short e_slot[GRAM_ENTRIES];   // hash slot per entry, NO_SLOT for dense/absent entries
     unsigned short start[GRAM_SLOTS];      // entries per slot, then exclusive scan = list begin
-    unsigned short post[GRAM_ENTRIES];     // posting lists: entry positions grouped by slot
-    const int32_t *r_col[TILE_W];
-    const float *r_val[TILE_W];
-    int r_len[TILE_W];
-    float r_sgn[TILE_W];
-    float r_scale[BATCH];
+    float post_val[GRAM_ENTRIES];          // posting lists grouped by slot: value ...
+    unsigned char post_row[GRAM_ENTRIES];  // ... and window row of each member
+    GramRows rows[2];                      // current tile, next tile
     int scan[GRAM_THREADS / 64];
 };
 
-constexpr unsigned short NO_SLOT = 0xffff;
 constexpr int EMPTY_KEY = -1;
 
 __device__ __forceinline__ int gram_hash(int col) { return (int)(((unsigned)col * 2654435761u) >> 19); }
+
+// Row lookups of one window, one row per thread (tid < 128), as four steps of dependent loads.
+struct RowLookup {
+    int lr, ci, r;
+    const int32_t *row_ptr, *colp;
+    const float *valp;
+    const RowState *stp;
+    int2_a4 rp;
+    float4_v st;
+    bool live;
+};
 
 // row_chunk[perm_off + lr] = chunk of the solver's local row lr; chunk_first[c] = local index of the
 // chunk's first row inside its solver.
@@ -49,148 +67,205 @@ template <int LOSS>
 __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ row_chunk, const int32_t *__restrict__ chunk_first,
-    const int32_t *__restrict__ perm, const int32_t *__restrict__ tile_solver, float *tiles, float c,
-    int *err)
+    const int32_t *__restrict__ perm, const int32_t *__restrict__ tile_solver, float *tiles, int n_tiles,
+    float c, int *err)
 {
     extern __shared__ __align__(16) unsigned char gsm[];
     GramShared &sh = *reinterpret_cast<GramShared *>(gsm);
-    const int tile = blockIdx.x;
-    const int k = tile_solver[tile];
-    const SolverDev S = solvers[k];
-    const int beta = tile - S.tile_begin;
     const int tid = threadIdx.x;
+    const int per = (n_tiles + gridDim.x - 1) / gridDim.x;
+    const int t_begin = blockIdx.x * per;
+    const int t_end = min(n_tiles, t_begin + per);
+    if (t_begin >= t_end) return;
 
-    // ---- rows of the window; clear the tables meanwhile
-    if (tid < TILE_W) {
+    const int32_t *dummy_col = chunks[0].col;      // readable for at least GRAM_MAX_ROW entries
+    const float *dummy_val = chunks[0].val;
+    RowLookup L;
+    SolverDev LS;
+    // step 1: visiting-order entry of this thread's row in window `tile`
+    auto lookup1 = [&](int tile) {
+        L.live = false; L.lr = -1;
+        if (tid >= TILE_W || tile >= t_end) return;
+        LS = solvers[tile_solver[tile]];
+        const int beta = tile - LS.tile_begin;
         const int b = tid < BATCH ? beta - 1 : beta;
         const int t = b * BATCH + (tid & (BATCH - 1));
+        if (b >= 0 && t < LS.n_rows) { L.lr = gld(perm + LS.perm_off + t); L.live = true; }
+    };
+    auto lookup2 = [&]() {       // -> chunk id
+        if (!L.live) return;
+        if ((unsigned)L.lr >= (unsigned)LS.n_rows) { atomicOr(err, ERR_PERM_RANGE); L.live = false; return; }
+        L.ci = gld(row_chunk + LS.perm_off + L.lr);
+    };
+    auto lookup3 = [&]() {       // -> chunk descriptor
+        if (!L.live) return;
+        const ChunkDev &ch = chunks[L.ci];
+        L.r = L.lr - gld(chunk_first + L.ci);
+        L.row_ptr = ch.row_ptr; L.colp = ch.col; L.valp = ch.val; L.stp = ch.st;
+    };
+    auto lookup4 = [&]() {       // -> row offsets and state
+        if (!L.live) return;
+        L.rp = gld2(L.row_ptr + L.r);
+        L.st = gld_state(L.stp + L.r);
+    };
+    auto publish = [&](GramRows &R) {
+        if (tid >= TILE_W) return;
         int len = 0;
         float sgn = 1.f, scale = 0.f;
         const int32_t *cp = nullptr;
         const float *vp = nullptr;
-        if (b >= 0 && t < S.n_rows) {
-            const int lr = perm[S.perm_off + t];
-            if ((unsigned)lr >= (unsigned)S.n_rows) {
-                atomicOr(err, ERR_PERM_RANGE);
-            } else {
-                const int ci = row_chunk[S.perm_off + lr];
-                const ChunkDev &ch = chunks[ci];
-                const int r = lr - chunk_first[ci];
-                const int rb = ch.row_ptr[r], re = ch.row_ptr[r + 1];
-                const RowState st = ch.st[r];
-                if (st.q != 0.f && re - rb <= GRAM_MAX_ROW) {
-                    len = re - rb; cp = ch.col + rb; vp = ch.val + rb;
-                    sgn = LOSS == 0 ? st.y : 1.f;
-                    scale = LOSS == 0 ? -1.f / st.q : -1.f / (c + st.q);
-                }
+        if (L.live) {
+            const int n = L.rp.y - L.rp.x;
+            const float q = L.st.z;
+            if (q != 0.f && n > 0 && n <= GRAM_MAX_ROW) {
+                len = n; cp = L.colp + L.rp.x; vp = L.valp + L.rp.x;
+                sgn = LOSS == 0 ? L.st.x : 1.f;
+                scale = LOSS == 0 ? -1.f / q : -1.f / (c + q);
             }
         }
-        sh.r_col[tid] = cp; sh.r_val[tid] = vp; sh.r_len[tid] = len; sh.r_sgn[tid] = sgn;
-        if (tid >= BATCH) sh.r_scale[tid - BATCH] = scale;
-    }
-    for (int i = tid; i < GRAM_SLOTS; i += GRAM_THREADS) { sh.keys[i] = EMPTY_KEY; sh.start[i] = 0; }
-    for (int i = tid; i < GRAM_DENSE * TILE_W; i += GRAM_THREADS) (&sh.A[0][0])[i] = 0.f;
+        if (len == 0) { cp = dummy_col; vp = dummy_val; }
+        R.col[tid] = cp; R.val[tid] = vp; R.len[tid] = len; R.sgn[tid] = sgn;
+        if (tid >= BATCH) R.scale[tid - BATCH] = scale;
+    };
+
+    lookup1(t_begin); lookup2(); lookup3(); lookup4(); publish(sh.rows[0]);
     __syncthreads();
 
-    // ---- stage the entries: dense part into A, the rest into the hash table (count per slot)
-    for (int idx = tid; idx < GRAM_ENTRIES; idx += GRAM_THREADS) {
-        const int s = idx / GRAM_MAX_ROW, p = idx - s * GRAM_MAX_ROW;
-        unsigned short slot = NO_SLOT;
-        if (p < sh.r_len[s]) {
-            const int col = gld(sh.r_col[s] + p);
-            const float v = gld(sh.r_val[s] + p);
-            if (col < GRAM_DENSE) {
-                sh.A[col][s] = v;
-            } else {
-                int h = gram_hash(col);
-                for (;;) {                       // ends: at most GRAM_ENTRIES < GRAM_SLOTS keys are inserted
-                    const int prev = atomicCAS(&sh.keys[h], EMPTY_KEY, col);
-                    if (prev == EMPTY_KEY || prev == col) break;
-                    h = (h + 1) & (GRAM_SLOTS - 1);
-                }
-                slot = (unsigned short)h;
-                sh.e_val[idx] = v;
-                // two 16-bit counters share a word
-                atomicAdd(reinterpret_cast<unsigned int *>(sh.start) + (h >> 1), (h & 1) ? 0x10000u : 1u);
-            }
-        }
-        sh.e_slot[idx] = slot;
-    }
-    __syncthreads();
-
-    // ---- exclusive scan of the slot counts (8 slots per thread), cursors into keys[]
-    {
-        const int base = tid * (GRAM_SLOTS / GRAM_THREADS);
-        int cnt[GRAM_SLOTS / GRAM_THREADS], sum = 0;
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        GramRows &R = sh.rows[(tile - t_begin) & 1];
+        // ---- issue this thread's entry loads; clear the tables; next tile's lookup, step 1
+        int e_col[GRAM_EPT];
+        float e_val[GRAM_EPT];
+        bool e_live[GRAM_EPT];
 #pragma unroll
-        for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) { cnt[j] = sh.start[base + j]; sum += cnt[j]; }
-        int incl = sum;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int y = __shfl_up(incl, o, 64);
-            if ((tid & 63) >= o) incl += y;
+        for (int k = 0; k < GRAM_EPT; ++k) {
+            const int idx = tid + k * GRAM_THREADS;
+            const int s = idx / GRAM_MAX_ROW, p = idx - s * GRAM_MAX_ROW;
+            // unconditional loads (a row without entries points at readable dummy data; the store keeps
+            // slack behind every chunk), masked by e_live afterwards
+            e_live[k] = p < R.len[s];
+            e_col[k] = gld(R.col[s] + p); e_val[k] = gld(R.val[s] + p);
         }
-        if ((tid & 63) == 63) sh.scan[tid >> 6] = incl;
+        lookup1(tile + 1);
+        for (int i = tid; i < GRAM_SLOTS; i += GRAM_THREADS) { sh.keys[i] = EMPTY_KEY; sh.start[i] = 0; }
+        for (int i = tid; i < GRAM_DENSE * TILE_W; i += GRAM_THREADS) (&sh.A[0][0])[i] = 0.f;
         __syncthreads();
-        int off = incl - sum;
-        for (int w = 0; w < (tid >> 6); ++w) off += sh.scan[w];
-#pragma unroll
-        for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) {
-            sh.start[base + j] = (unsigned short)off;
-            sh.keys[base + j] = off;
-            off += cnt[j];
-        }
-    }
-    __syncthreads();
 
-    // ---- fill the posting lists
-    for (int idx = tid; idx < GRAM_ENTRIES; idx += GRAM_THREADS) {
-        const unsigned short slot = sh.e_slot[idx];
-        if (slot != NO_SLOT) {
-            const int pos = atomicAdd(&sh.keys[slot], 1);
-            sh.post[pos] = (unsigned short)idx;
+        // ---- dense part into A, the rest into the hash table (count per slot)
+        int e_slot[GRAM_EPT], first[GRAM_EPT];
+#pragma unroll
+        for (int k = 0; k < GRAM_EPT; ++k) {       // first probes of all entries in flight together
+            const int idx = tid + k * GRAM_THREADS;
+            const int s = idx / GRAM_MAX_ROW;
+            e_slot[k] = -1; first[k] = EMPTY_KEY;
+            if (e_live[k]) {
+                if (e_col[k] < GRAM_DENSE) sh.A[e_col[k]][s] = e_val[k];
+                else {
+                    e_slot[k] = gram_hash(e_col[k]);
+                    first[k] = atomicCAS(&sh.keys[e_slot[k]], EMPTY_KEY, e_col[k]);
+                }
+            }
         }
-    }
-    // ---- dense part: G[jp][i] = sum_h A[h][64 + i] A[h][jp]; thread -> 4 values of i, 2 of jp
-    {
-        const int i0 = (tid & 15) * 4, j0 = (tid >> 4) * 2;
-        float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int k = 0; k < GRAM_EPT; ++k) {
+            if (e_slot[k] < 0) continue;
+            int h = e_slot[k], prev = first[k];
+            while (prev != EMPTY_KEY && prev != e_col[k]) {   // ends: fewer keys than slots are inserted
+                h = (h + 1) & (GRAM_SLOTS - 1);
+                prev = atomicCAS(&sh.keys[h], EMPTY_KEY, e_col[k]);
+            }
+            e_slot[k] = h;
+            // two 16-bit counters share a word
+            atomicAdd(reinterpret_cast<unsigned int *>(sh.start) + (h >> 1), (h & 1) ? 0x10000u : 1u);
+        }
+        lookup2();
+        __syncthreads();
+
+        // ---- exclusive scan of the slot counts (8 slots per thread), cursors into keys[]
+        {
+            const int base = tid * (GRAM_SLOTS / GRAM_THREADS);
+            int cnt[GRAM_SLOTS / GRAM_THREADS], sum = 0;
+#pragma unroll
+            for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) { cnt[j] = sh.start[base + j]; sum += cnt[j]; }
+            int incl = sum;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int y = __shfl_up(incl, o, 64);
+                if ((tid & 63) >= o) incl += y;
+            }
+            if ((tid & 63) == 63) sh.scan[tid >> 6] = incl;
+            __syncthreads();
+            int off = incl - sum;
+            for (int w = 0; w < (tid >> 6); ++w) off += sh.scan[w];
+#pragma unroll
+            for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) {
+                sh.start[base + j] = (unsigned short)off;
+                sh.keys[base + j] = off;
+                off += cnt[j];
+            }
+        }
+        lookup3();
+        __syncthreads();
+
+        // ---- fill the posting lists
+#pragma unroll
+        for (int k = 0; k < GRAM_EPT; ++k)
+            if (e_slot[k] >= 0) {
+                const int pos = atomicAdd(&sh.keys[e_slot[k]], 1);
+                sh.post_val[pos] = e_val[k];
+                sh.post_row[pos] = (unsigned char)((tid + k * GRAM_THREADS) / GRAM_MAX_ROW);
+            }
+        // ---- dense part: G[jp][i] = sum_h A[h][64 + i] A[h][jp]; thread -> 4 values of i, 2 of jp
+        {
+            const int i0 = (tid & 15) * 4, j0 = (tid >> 4) * 2;
+            float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll 8
-        for (int h = 0; h < GRAM_DENSE; ++h) {
-            const float4 ai = *reinterpret_cast<const float4 *>(&sh.A[h][BATCH + i0]);
-            const float2 aj = *reinterpret_cast<const float2 *>(&sh.A[h][j0]);
-            acc[0][0] += aj.x * ai.x; acc[0][1] += aj.x * ai.y; acc[0][2] += aj.x * ai.z; acc[0][3] += aj.x * ai.w;
-            acc[1][0] += aj.y * ai.x; acc[1][1] += aj.y * ai.y; acc[1][2] += aj.y * ai.z; acc[1][3] += aj.y * ai.w;
-        }
+            for (int h = 0; h < GRAM_DENSE; ++h) {
+                const float4 ai = *reinterpret_cast<const float4 *>(&sh.A[h][BATCH + i0]);
+                const float2 aj = *reinterpret_cast<const float2 *>(&sh.A[h][j0]);
+                acc[0][0] += aj.x * ai.x; acc[0][1] += aj.x * ai.y; acc[0][2] += aj.x * ai.z; acc[0][3] += aj.x * ai.w;
+                acc[1][0] += aj.y * ai.x; acc[1][1] += aj.y * ai.y; acc[1][2] += aj.y * ai.z; acc[1][3] += aj.y * ai.w;
+            }
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) sh.G[j0 + a][i0 + b] = acc[a][b];
-    }
-    __syncthreads();
-
-    // ---- sparse part: every entry of a block row meets the other entries of its column
-    for (int idx = BATCH * GRAM_MAX_ROW + tid; idx < GRAM_ENTRIES; idx += GRAM_THREADS) {
-        const unsigned short slot = sh.e_slot[idx];
-        if (slot == NO_SLOT) continue;
-        const int i = idx / GRAM_MAX_ROW - BATCH;
-        const float a = sh.e_val[idx];
-        const int pb = sh.start[slot], pe = sh.keys[slot];
-        for (int p = pb; p < pe; ++p) {
-            const int f = sh.post[p];
-            const int sf = f / GRAM_MAX_ROW;
-            if (sf < BATCH || sf - BATCH < i) atomicAdd(&sh.G[sf][i], a * sh.e_val[f]);
+                for (int b = 0; b < 4; ++b) sh.G[j0 + a][i0 + b] = acc[a][b];
         }
-    }
-    __syncthreads();
+        lookup4();
+        __syncthreads();
 
-    // ---- scale and write out, coalesced over i
-    float *out = tiles + (int64_t)tile * TILE_FLOATS;
-    for (int idx = tid; idx < TILE_FLOATS; idx += GRAM_THREADS) {
-        const int jp = idx >> 6, i = idx & 63;
-        float g = 0.f;
-        if (jp < BATCH || jp - BATCH < i) g = sh.G[jp][i] * sh.r_scale[i] * sh.r_sgn[BATCH + i] * sh.r_sgn[jp];
-        out[idx] = g;
+        // ---- sparse part: every entry of a block row meets the other members of its column's list
+#pragma unroll
+        for (int k = GRAM_EPT / 2; k < GRAM_EPT; ++k) {          // positions of the block rows (64 .. 127)
+            if (e_slot[k] < 0) continue;
+            const int i = (tid + k * GRAM_THREADS) / GRAM_MAX_ROW - BATCH;
+            const float a = e_val[k];
+            const int pb = sh.start[e_slot[k]], pe = sh.keys[e_slot[k]];
+            for (int p = pb; p < pe; p += 4) {          // four list members per round of LDS latency
+                int sf[4];
+                float vf[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int pj = min(p + j, pe - 1);
+                    sf[j] = sh.post_row[pj]; vf[j] = sh.post_val[pj];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (p + j < pe && (sf[j] < BATCH || sf[j] - BATCH < i)) atomicAdd(&sh.G[sf[j]][i], a * vf[j]);
+            }
+        }
+        publish(sh.rows[(tile + 1 - t_begin) & 1]);
+        __syncthreads();
+
+        // ---- scale and write out, coalesced over i
+        float *out = tiles + (int64_t)tile * TILE_FLOATS;
+        for (int idx = tid; idx < TILE_FLOATS; idx += GRAM_THREADS) {
+            const int jp = idx >> 6, i = idx & 63;
+            float g = 0.f;
+            if (jp < BATCH || jp - BATCH < i) g = sh.G[jp][i] * R.scale[i] * R.sgn[BATCH + i] * R.sgn[jp];
+            out[idx] = g;
+        }
+        // the next iteration's first barrier separates this read of G and R from their next writes
     }
 }
 

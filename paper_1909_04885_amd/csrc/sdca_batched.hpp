@@ -29,7 +29,8 @@ constexpr int GRAM_MAX_ROW = 48;             // longest sparse row the batched s
 constexpr int LPR = 8;                       // helper lanes per row
 constexpr int ENT = GRAM_MAX_ROW / LPR;      // entries per helper lane (6: one 16-byte and one 8-byte load)
 constexpr int HELPER_WAVES = BATCH * LPR / 64;
-constexpr int BATCHED_THREADS = 64 + BATCH * LPR;
+constexpr int SERVICE_WAVES = 2;              // row resolution and tile staging
+constexpr int BATCHED_THREADS = 64 + BATCH * LPR + 64 * SERVICE_WAVES;
 constexpr int RING = 8;
 constexpr int HOT_COLS = 12288;               // head of the private vector kept in LDS (popular columns)
 
@@ -127,7 +128,8 @@ __device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, 
     x_carry = x;
 }
 
-// One workgroup per solver: wavefront 0 runs the chain, the others gather, scatter and stage.
+// One workgroup per solver: wavefront 0 runs the chain, eight wavefronts gather and scatter, two
+// resolve the rows of coming blocks and stage the tiles.
 // Dynamic LDS: BatchedShared, then max_list chunk descriptors, max_list local-row prefixes, n_hot floats.
 template <int LOSS>
 __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
@@ -155,17 +157,19 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const int32_t *pk = perm + S.perm_off;
     const float *my_tiles = tiles + (int64_t)S.tile_begin * TILE_FLOATS;
     const int nb = (S.n_rows + BATCH - 1) / BATCH;
+    // roles: wavefront 0 runs the chain, 1..8 gather and scatter, 9..10 resolve rows and stage tiles
     const bool is_chain = tid < 64;
+    const bool is_service = tid >= 64 + BATCH * LPR;
     const int lane = tid & 63;
-    // helper coordinates
-    const int hl = tid - 64, rho = hl >> 3, sub = hl & (LPR - 1);
+    const int hl = tid - 64, rho = hl >> 3, sub = hl & (LPR - 1);     // helper coordinates
+    const int sw = (tid - 64 - BATCH * LPR) >> 6;                     // service wavefront 0 or 1
 
-    // helper pipeline registers
-    int p_cur = -1, p_next = -1;                     // visiting-order entries (meta lanes: hl < 64)
+    // service pipeline registers (wavefront 9: one lane per row of a block)
+    int p_cur = -1, p_next = -1;                     // visiting-order entries
     int m_ci = -1, m_r = 0;                          // row being resolved: loads in flight
     int2_a4 m_rp = {0, 0};
     float4_v m_st = {0.f, 0.f, 0.f, 0.f};          // kept whole until it is used (y, alpha, q, zw)
-    // Entries of a row segment (ENT consecutive entries per lane) travel through four stages:
+    // Entries of a row segment (ENT consecutive entries per helper lane) travel through four stages:
     // in (loads in flight) -> g (gathered this iteration) -> c (its block is in the chain) -> s (scattered).
     int in_c[ENT], g_c[ENT], c_c[ENT], s_c[ENT];
     float in_v[ENT], g_v[ENT], c_v[ENT], s_v[ENT];
@@ -178,44 +182,64 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     float x_carry = 0.f;
     int hb_target = 0;
     if (nb == 0) return;                             // a solver without rows (uniform for the workgroup)
-    const bool meta = !is_chain && hl < BATCH;       // one helper wavefront resolves the 64 rows of a block
 
     for (int i = -5; i <= nb; ++i) {
         if (is_chain) {
             if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry);
+        } else if (is_service) {
+            // tiles for iteration i + 1: wavefront 9 stages the own part of T(i+1), wavefront 10 the
+            // cross part of T(i+2); 16 KB each, all loads in flight before the first LDS write
+            const int tb = sw == 0 ? i + 1 : i + 2;
+            const bool have = tb >= 0 && tb < nb;
+            float4 stage[16];
+            if (have) {
+                const float4 *src = reinterpret_cast<const float4 *>(
+                    my_tiles + (int64_t)tb * TILE_FLOATS + (sw == 0 ? BATCH * BATCH : 0));
+#pragma unroll
+                for (int j = 0; j < 16; ++j) stage[j] = src[lane + 64 * j];
+            }
+            if (sw == 0) {
+                // 1. publish the row of block i + 3 whose state loads were issued last iteration
+                if (i + 3 >= 0 && i + 3 < nb) {
+                    RowSlot s;
+                    s.col = l_desc[0].col; s.val = l_desc[0].val; s.st = nullptr; s.len = 0;
+                    s.y = m_st.x; s.alpha = m_st.y; s.q = m_st.z; s.zw = m_st.w;
+                    const int len = m_rp.y - m_rp.x;
+                    if (m_ci >= 0 && s.q != 0.f && len > 0 && len <= GRAM_MAX_ROW) {
+                        const ChunkDev &ch = l_desc[m_ci];
+                        s.col = ch.col + m_rp.x; s.val = ch.val + m_rp.x; s.st = ch.st + m_r;
+                        s.len = len;
+                    }
+                    sh.rows[(i + 3) & (RING - 1)][lane] = s;
+                }
+                // 2. issue the state loads of block i + 4 from the order entry read last iteration
+                m_ci = -1;
+                if (i + 4 >= 0 && i + 4 < nb && p_cur >= 0) {
+                    if (p_cur >= S.n_rows) {
+                        atomicOr(err, ERR_PERM_RANGE);
+                    } else {
+                        m_ci = find_chunk(l_prefix, S.n_chunks, p_cur);
+                        m_r = p_cur - l_prefix[m_ci];
+                        const ChunkDev &ch = l_desc[m_ci];
+                        m_rp = gld2(ch.row_ptr + m_r);
+                        m_st = gld_state(ch.st + m_r);
+                    }
+                }
+                // 3. read the order entry of block i + 5
+                p_next = -1;
+                if (i + 5 >= 0 && i + 5 < nb) {
+                    const int t = (i + 5) * BATCH + lane;
+                    if (t < S.n_rows) p_next = pk[t];
+                }
+                p_cur = p_next;
+            }
+            {
+                const int buf = (i + 1) & 1;
+                float4 *dst = reinterpret_cast<float4 *>(sw == 0 ? &sh.Tw[buf][0][0] : &sh.Tx[buf][0][0]);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dst[lane + 64 * j] = have ? stage[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         } else {
-            // 1. publish the row of block i + 3 whose state loads were issued last iteration
-            if (meta && i + 3 >= 0 && i + 3 < nb) {
-                RowSlot s;
-                s.col = l_desc[0].col; s.val = l_desc[0].val; s.st = nullptr; s.len = 0;
-                s.y = m_st.x; s.alpha = m_st.y; s.q = m_st.z; s.zw = m_st.w;
-                const int len = m_rp.y - m_rp.x;
-                if (m_ci >= 0 && s.q != 0.f && len > 0 && len <= GRAM_MAX_ROW) {
-                    const ChunkDev &ch = l_desc[m_ci];
-                    s.col = ch.col + m_rp.x; s.val = ch.val + m_rp.x; s.st = ch.st + m_r;
-                    s.len = len;
-                }
-                sh.rows[(i + 3) & (RING - 1)][hl] = s;
-            }
-            // 2. issue the state loads of block i + 4 from the order entry read last iteration
-            m_ci = -1;
-            if (meta && i + 4 >= 0 && i + 4 < nb && p_cur >= 0) {
-                if (p_cur >= S.n_rows) {
-                    atomicOr(err, ERR_PERM_RANGE);
-                } else {
-                    m_ci = find_chunk(l_prefix, S.n_chunks, p_cur);
-                    m_r = p_cur - l_prefix[m_ci];
-                    const ChunkDev &ch = l_desc[m_ci];
-                    m_rp = gld2(ch.row_ptr + m_r);
-                    m_st = gld_state(ch.st + m_r);
-                }
-            }
-            // 3. read the order entry of block i + 5
-            p_next = -1;
-            if (meta && i + 5 >= 0 && i + 5 < nb) {
-                const int t = (i + 5) * BATCH + hl;
-                if (t < S.n_rows) p_next = pk[t];
-            }
             // 4. fetch this lane's segment of the row of block i + 2 (unconditional vector loads; the
             //    entries beyond the row's length are masked when the set moves on)
             if (i + 2 >= 0 && i + 2 < nb) {
@@ -231,17 +255,6 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 in_v[0] = v4.x; in_v[1] = v4.y; in_v[2] = v4.z; in_v[3] = v4.w; in_v[4] = v2.x; in_v[5] = v2.y;
             } else {
                 in_len = 0;
-            }
-            // tile staging loads for iteration i + 1: own part of T(i+1), cross part of T(i+2)
-            float4 tw_a = make_float4(0.f, 0.f, 0.f, 0.f), tw_b = tw_a, tx_a = tw_a, tx_b = tw_a;
-            if (i + 1 >= 0 && i + 1 < nb) {
-                const float4 *src = reinterpret_cast<const float4 *>(
-                    my_tiles + (int64_t)(i + 1) * TILE_FLOATS + BATCH * BATCH);
-                tw_a = src[hl]; tw_b = src[hl + 512];
-            }
-            if (i + 2 >= 0 && i + 2 < nb) {
-                const float4 *src = reinterpret_cast<const float4 *>(my_tiles + (int64_t)(i + 2) * TILE_FLOATS);
-                tx_a = src[hl]; tx_b = src[hl + 512];
             }
             // 5. scatter block i - 1: alpha and the private vector (masked entries carry value 0)
             if (i - 1 >= 0 && i - 1 < nb) {
@@ -299,15 +312,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;
                 }
             }
-            // 8. publish the staged tile parts for iteration i + 1
-            {
-                const int buf = (i + 1) & 1;
-                float4 *dw = reinterpret_cast<float4 *>(&sh.Tw[buf][0][0]);
-                float4 *dx = reinterpret_cast<float4 *>(&sh.Tx[buf][0][0]);
-                dw[hl] = tw_a; dw[hl + 512] = tw_b;
-                dx[hl] = tx_a; dx[hl + 512] = tx_b;
-            }
-            // 9. move the entry sets one stage on; the incoming set is masked to the row's length
+            // 8. move the entry sets one stage on; the incoming set is masked to the row's length
 #pragma unroll
             for (int e = 0; e < ENT; ++e) {
                 s_c[e] = c_c[e]; s_v[e] = c_v[e];
@@ -316,7 +321,6 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 g_c[e] = live ? in_c[e] : 0;
                 g_v[e] = live ? in_v[e] : 0.f;
             }
-            p_cur = p_next;
         }
         __syncthreads();
     }
