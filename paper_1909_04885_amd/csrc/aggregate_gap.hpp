@@ -17,13 +17,15 @@ __global__ __launch_bounds__(256) void clear_private(float *u_all, int64_t ld_v,
 }
 
 // w <- w + sum_k Delta w_k with Delta w_k = u_k / sigma, then u_k <- 0 for all k (merge, broadcast).
-// One pass: reads K + 1 vectors, writes K + 1 vectors, four columns per thread (ld_v and the
+// The shared vector is kept in double (w64) with a float mirror (w32) for the kernels that gather it.
+// One pass: reads K + 1 vectors, writes K + 2 vectors, four columns per thread (ld_v and the
 // buffers are 16-byte aligned; d is handled up to its padded length, the padding holds zeros).
-__global__ __launch_bounds__(256) void aggregate_broadcast(float *w, float *u_all, int64_t ld_v,
-                                                           int64_t d4, int K, float inv_sigma)
+__global__ __launch_bounds__(256) void aggregate_broadcast(double *w64, float *w32, float *u_all,
+                                                           int64_t ld_v, int64_t d4, int K, float inv_sigma)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    float4 *w4 = reinterpret_cast<float4 *>(w);
+    double2 *wd = reinterpret_cast<double2 *>(w64);
+    float4 *wf = reinterpret_cast<float4 *>(w32);
     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d4; j += stride) {
         float4 acc = z;
@@ -33,10 +35,11 @@ __global__ __launch_bounds__(256) void aggregate_broadcast(float *w, float *u_al
             acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
             *uk = z;
         }
-        float4 o = w4[j];
-        o.x += acc.x * inv_sigma; o.y += acc.y * inv_sigma;
-        o.z += acc.z * inv_sigma; o.w += acc.w * inv_sigma;
-        w4[j] = o;
+        double2 lo = wd[2 * j], hi = wd[2 * j + 1];
+        lo.x += (double)(acc.x * inv_sigma); lo.y += (double)(acc.y * inv_sigma);
+        hi.x += (double)(acc.z * inv_sigma); hi.y += (double)(acc.w * inv_sigma);
+        wd[2 * j] = lo; wd[2 * j + 1] = hi;
+        wf[j] = make_float4((float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y);
     }
 }
 
@@ -75,17 +78,37 @@ __device__ __forceinline__ void block_sum2_store(double a, double b, double *out
     }
 }
 
-// Per-row loss and conjugate terms of the gap, sparse rows; also leaves z_i = x_i . w in the chunk
-// (zw) for the next local pass.  LPR lanes cooperate on one row
-// (LPR divides 64).  Work items are blocks of 256/LPR rows of one chunk; item_prefix[c] = first
-// item of chunk c.  Each workgroup writes one partial (loss sum, conjugate sum) in double.
+// Per-row loss and conjugate terms of the gap; also leaves the residual rw of every row in the chunk
+// for the next local pass (hinge: 1 - y z, squared: y - z with z = x_i . w).  WT is the type the dot
+// product is gathered and accumulated in: double for the squared loss, whose steps cancel y - z - alpha
+// down to the size of the update near convergence; float for hinge.
+// LPR lanes cooperate on one row (LPR divides 64).  Work items are blocks of 256/LPR rows of one chunk;
+// item_prefix[c] = first item of chunk c.  Each workgroup writes one partial (loss sum, conjugate sum)
+// in double.
 //   hinge   : loss = max(0, 1 - y z),   conj = loss^*(-a) = -a
 //   squared : loss = (z - y)^2 / 2,     conj = a^2/2 - a y
-template <int LOSS, int LPR>
+template <int LOSS, typename WT>
+__device__ __forceinline__ void gap_row_terms(RowState *st, WT z, double &s_loss, double &s_conj)
+{
+    const float y = st->y, a = st->alpha;
+    if (LOSS == 0) {
+        const WT rw = (WT)1 - (WT)y * z;
+        st->rw = (float)rw;
+        s_loss += (double)(rw > (WT)0 ? rw : (WT)0);
+        s_conj += (double)(-a);
+    } else {
+        const WT rw = (WT)y - z;
+        st->rw = (float)rw;
+        s_loss += 0.5 * (double)rw * (double)rw;
+        s_conj += 0.5 * (double)a * (double)a - (double)a * (double)y;
+    }
+}
+
+template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__ chunks,
                                                     const int32_t *__restrict__ item_prefix,
                                                     int n_chunks, int total_items,
-                                                    const float *__restrict__ w,
+                                                    const WT *__restrict__ w,
                                                     double *part_loss, double *part_conj)
 {
     constexpr int ROWS = 256 / LPR;
@@ -96,36 +119,25 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
         const int c = find_chunk(item_prefix, n_chunks, item);
         const ChunkDev &ch = chunks[c];
         const int r = (item - item_prefix[c]) * ROWS + rloc;
-        float z = 0.f;
+        WT z = 0;
         const bool live = r < ch.n_rows;
         if (live) {
             const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-            for (int p = b + sub; p < e; p += LPR) z += ch.val[p] * w[ch.col[p]];
+            for (int p = b + sub; p < e; p += LPR) z += (WT)ch.val[p] * w[ch.col[p]];
         }
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
-        if (live && sub == 0) {
-            const float y = ch.st[r].y, a = ch.st[r].alpha;
-            ch.st[r].zw = z;
-            if (LOSS == 0) {
-                s_loss += (double)fmaxf(0.f, 1.f - y * z);
-                s_conj += (double)(-a);
-            } else {
-                const float rr = z - y;
-                s_loss += 0.5 * (double)rr * (double)rr;
-                s_conj += 0.5 * (double)a * (double)a - (double)a * (double)y;
-            }
-        }
+        if (live && sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
     }
     block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
 }
 
-// Dense rows: one wavefront-quarter (LPR lanes) per row, strided over the d columns.
-template <int LOSS, int LPR>
+// Dense rows: LPR lanes per row, strided over the d columns.
+template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks,
                                                       const int32_t *__restrict__ item_prefix,
                                                       int n_chunks, int total_items, int d,
-                                                      const float *__restrict__ w,
+                                                      const WT *__restrict__ w,
                                                       double *part_loss, double *part_conj)
 {
     constexpr int ROWS = 256 / LPR;
@@ -136,38 +148,27 @@ __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict
         const int c = find_chunk(item_prefix, n_chunks, item);
         const ChunkDev &ch = chunks[c];
         const int r = (item - item_prefix[c]) * ROWS + rloc;
-        float z = 0.f;
+        WT z = 0;
         const bool live = r < ch.n_rows;
         if (live) {
             const float *x = ch.val + (int64_t)r * d;
-            for (int p = sub; p < d; p += LPR) z += x[p] * w[p];
+            for (int p = sub; p < d; p += LPR) z += (WT)x[p] * w[p];
         }
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
-        if (live && sub == 0) {
-            const float y = ch.st[r].y, a = ch.st[r].alpha;
-            ch.st[r].zw = z;
-            if (LOSS == 0) {
-                s_loss += (double)fmaxf(0.f, 1.f - y * z);
-                s_conj += (double)(-a);
-            } else {
-                const float rr = z - y;
-                s_loss += 0.5 * (double)rr * (double)rr;
-                s_conj += 0.5 * (double)a * (double)a - (double)a * (double)y;
-            }
-        }
+        if (live && sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
     }
     block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
 }
 
 // |w|^2 partials in double.
-__global__ __launch_bounds__(256) void wsq_partial(const float *__restrict__ w, int64_t d,
+__global__ __launch_bounds__(256) void wsq_partial(const double *__restrict__ w, int64_t d,
                                                    double *part_wsq, double *part_unused)
 {
     double s = 0.0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
-        const double x = (double)w[j];
+        const double x = w[j];
         s += x * x;
     }
     block_sum2_store(s, 0.0, &part_wsq[blockIdx.x], &part_unused[blockIdx.x]);

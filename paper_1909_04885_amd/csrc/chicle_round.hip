@@ -65,7 +65,8 @@ struct chicle_ctx {
     ChunkDev *chunks_dev = nullptr;
     SolverDev *solvers_dev = nullptr;
     int32_t *solver_chunks_dev = nullptr, *solver_prefix_dev = nullptr, *item_prefix_dev = nullptr;
-    float *w = nullptr;        // shared vector (internal column order)
+    double *w64 = nullptr;     // shared vector (internal column order), double precision
+    float *w = nullptr;        // its float mirror, gathered by the float kernels
     float *u = nullptr;        // private vectors as differences u_k = v_k - w, max_solvers x ld_v
     float *tmp_a = nullptr, *tmp_b = nullptr;   // d floats each: staging of host transfers
     int32_t *rank_of = nullptr, *col_of = nullptr;   // column renumbering tables (device)
@@ -76,7 +77,7 @@ struct chicle_ctx {
     int32_t *row_chunk_dev = nullptr, *chunk_first_dev = nullptr, *list_base_dev = nullptr;
     int64_t max_tiles = 0;
     int32_t n_tiles = 0;
-    bool zw_valid = true;      // zw = X w holds trivially for w = 0 after loading
+    bool zw_valid = true;      // the rows' residuals match w (set at load time for w = 0)
     int32_t *perm_stage = nullptr;
     double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
            *gap_out = nullptr;
@@ -138,6 +139,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);
     s += align_up(sizeof(int32_t) * ((size_t)n_chunks + 1));
     s += align_up(sizeof(float) * (size_t)ld) * 3;                       // w, tmp_a, tmp_b
+    s += align_up(sizeof(double) * (size_t)ld);                          // w in double
     s += align_up(sizeof(float) * (size_t)ld * (size_t)max_solvers);     // private vectors
     s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
     s += align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
@@ -293,16 +295,25 @@ int launch_batched(chicle_ctx *c, const int32_t *perm)
     return CHICLE_OK;
 }
 
+template <int LOSS, int LPRG, typename WT>
+void launch_gap_rows_t(chicle_ctx *c, int grid, const WT *w)
+{
+    if (c->dense)
+        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+                           c->item_prefix_dev, c->n_chunks, c->gap_items, (int)c->d, w, c->part_loss,
+                           c->part_conj);
+    else
+        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
+                           c->item_prefix_dev, c->n_chunks, c->gap_items, w, c->part_loss, c->part_conj);
+}
+
+// Squared loss: dot products in double against the double w (its steps cancel y - z - alpha down to the
+// size of the update); hinge: float against the float mirror.
 template <int LOSS, int LPRG>
 void launch_gap_rows(chicle_ctx *c, int grid)
 {
-    if (c->dense)
-        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
-                           c->item_prefix_dev, c->n_chunks, c->gap_items, (int)c->d, c->w, c->part_loss,
-                           c->part_conj);
-    else
-        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
-                           c->item_prefix_dev, c->n_chunks, c->gap_items, c->w, c->part_loss, c->part_conj);
+    if (LOSS == 1) launch_gap_rows_t<LOSS, LPRG, double>(c, grid, c->w64);
+    else launch_gap_rows_t<LOSS, LPRG, float>(c, grid, c->w);
 }
 
 template <int LOSS>
@@ -429,6 +440,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->solver_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     c->item_prefix_dev = (int32_t *)carve(c, sizeof(int32_t) * ((size_t)n_chunks + 1));
     c->w = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
+    c->w64 = (double *)carve(c, sizeof(double) * (size_t)c->ld_v);
     c->tmp_a = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
     c->tmp_b = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
     c->u = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
@@ -451,6 +463,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
     bool ok = hipMemsetAsync(c->w, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->w64, 0, sizeof(double) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->tmp_a, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->tmp_b, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
@@ -502,7 +515,8 @@ static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const floa
     ch.st = sd;
     std::vector<RowState> st(ch.n_rows);
     for (int32_t r = 0; r < ch.n_rows; ++r) {
-        st[r].y = y[r]; st[r].alpha = alpha0 ? alpha0[r] : 0.f; st[r].q = q[r]; st[r].zw = 0.f;
+        st[r].y = y[r]; st[r].alpha = alpha0 ? alpha0[r] : 0.f; st[r].q = q[r];
+        st[r].rw = c->loss == CHICLE_LOSS_HINGE ? 1.f : y[r];   // residual at w = 0
     }
     HIP_TRY(c, hipMemcpyAsync(sd, st.data(), nb, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));   // host arrays are the caller's again on return
@@ -745,7 +759,7 @@ int chicle_aggregate(chicle_ctx *c)
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "no local epoch pending");
     seg_begin(c, CHICLE_SEG_AGGREGATE);
     const int64_t d4 = c->ld_v / 4;
-    hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w,
+    hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w64, c->w,
                        c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
     seg_end(c, CHICLE_SEG_AGGREGATE);
     HIP_TRY(c, hipGetLastError());
@@ -763,7 +777,7 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     int rc = run_row_pass(c, &grid);
     if (rc) return rc;
     const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
-    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w, (int64_t)c->d, c->part_wsq, c->part_unused);
+    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, c->part_wsq, c->part_unused);
     hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, c->part_loss, c->part_conj, grid,
                        c->part_wsq, gw, c->gap_out);
     seg_end(c, CHICLE_SEG_GAP);
@@ -784,7 +798,7 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
 // d floats in internal order on the device -> caller's order on the host.
 static int read_vector(chicle_ctx *c, const float *src_internal, float scale, float *host_out)
 {
-    hipLaunchKernelGGL(to_caller_order, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream,
+    hipLaunchKernelGGL(to_caller_order<float>, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream,
                        src_internal, c->renumbered ? c->col_of : (const int32_t *)nullptr, (int64_t)c->d,
                        scale, c->tmp_b);
     HIP_TRY(c, hipGetLastError());
@@ -807,7 +821,7 @@ int chicle_set_w(chicle_ctx *c, const float *w_in)
         if (!std::isfinite(w_in[j])) return fail(c, CHICLE_EINVAL, "w not finite at %d", j);
     HIP_TRY(c, hipMemcpyAsync(c->tmp_b, w_in, sizeof(float) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));
     hipLaunchKernelGGL(from_caller_order, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->tmp_b,
-                       c->renumbered ? c->col_of : (const int32_t *)nullptr, (int64_t)c->d, c->w);
+                       c->renumbered ? c->col_of : (const int32_t *)nullptr, (int64_t)c->d, c->w64, c->w);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->zw_valid = false;

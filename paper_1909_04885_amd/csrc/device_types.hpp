@@ -10,7 +10,8 @@ struct RowState {
     float y;        // label / target
     float alpha;    // dual variable
     float q;        // squared row norm
-    float zw;       // x_i . w at the current shared vector (refreshed by the gap pass)
+    float rw;       // residual at the current shared vector, refreshed by the gap pass in double:
+                    // 1 - y x_i.w (hinge), y - x_i.w (squared)
 };
 
 // One data chunk as the kernels see it (paper Section 4.4: sparse or dense rows plus per-sample

@@ -44,23 +44,27 @@ __global__ __launch_bounds__(256) void renumber_rows(const ChunkDev *__restrict_
 }
 
 // out[col_of[r]] = in[r] * scale (internal order -> caller's column ids).
-__global__ __launch_bounds__(256) void to_caller_order(const float *__restrict__ in,
+template <typename T>
+__global__ __launch_bounds__(256) void to_caller_order(const T *__restrict__ in,
                                                        const int32_t *__restrict__ col_of, int64_t d,
                                                        float scale, float *out)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < d; r += stride)
-        out[col_of ? col_of[r] : r] = in[r] * scale;
+        out[col_of ? col_of[r] : r] = (float)in[r] * scale;
 }
 
-// out[r] = in[col_of[r]] (caller's column ids -> internal order).
+// out64[r] = out32[r] = in[col_of[r]] (caller's column ids -> internal order).
 __global__ __launch_bounds__(256) void from_caller_order(const float *__restrict__ in,
                                                          const int32_t *__restrict__ col_of, int64_t d,
-                                                         float *out)
+                                                         double *out64, float *out32)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < d; r += stride)
-        out[r] = in[col_of ? col_of[r] : r];
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < d; r += stride) {
+        const float x = in[col_of ? col_of[r] : r];
+        out64[r] = (double)x;
+        out32[r] = x;
+    }
 }
 
 }  // namespace chicle

@@ -57,7 +57,7 @@ struct RowSlot {
     const float *val;
     RowState *st;
     int len;              // 0 for a missing, empty or rejected row
-    float y, alpha, q, zw;
+    float y, alpha, q, rw;
 };
 
 // Resolve local row lr of a solver (lists in global memory) into a RowSlot; len = 0 if unusable.
@@ -67,7 +67,7 @@ __device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunk
 {
     RowSlot s;
     s.col = nullptr; s.val = nullptr; s.st = nullptr; s.len = 0;
-    s.y = 0.f; s.alpha = 0.f; s.q = 0.f; s.zw = 0.f;
+    s.y = 0.f; s.alpha = 0.f; s.q = 0.f; s.rw = 0.f;
     if (lr < 0) return s;
     if (lr >= n_rows) { atomicOr(err, ERR_PERM_RANGE); return s; }
     const int j = find_chunk(l_prefix, n_list, lr);
@@ -78,7 +78,7 @@ __device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunk
     s.q = st.q;
     if (s.q == 0.f || e - b > GRAM_MAX_ROW) return s;
     s.col = ch.col + b; s.val = ch.val + b; s.st = ch.st + r; s.len = e - b;
-    s.y = st.y; s.alpha = st.alpha; s.zw = st.zw;
+    s.y = st.y; s.alpha = st.alpha; s.rw = st.rw;
     return s;
 }
 
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     int p_cur = -1, p_next = -1;                     // visiting-order entries
     int m_ci = -1, m_r = 0;                          // row being resolved: loads in flight
     int2_a4 m_rp = {0, 0};
-    float4_v m_st = {0.f, 0.f, 0.f, 0.f};          // kept whole until it is used (y, alpha, q, zw)
+    float4_v m_st = {0.f, 0.f, 0.f, 0.f};          // kept whole until it is used (y, alpha, q, rw)
     // Entries of a row segment (ENT consecutive entries per helper lane) travel through four stages:
     // in (loads in flight) -> g (gathered this iteration) -> c (its block is in the chain) -> s (scattered).
     int in_c[ENT], g_c[ENT], c_c[ENT], s_c[ENT];
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 if (i + 3 >= 0 && i + 3 < nb) {
                     RowSlot s;
                     s.col = l_desc[0].col; s.val = l_desc[0].val; s.st = nullptr; s.len = 0;
-                    s.y = m_st.x; s.alpha = m_st.y; s.q = m_st.z; s.zw = m_st.w;
+                    s.y = m_st.x; s.alpha = m_st.y; s.q = m_st.z; s.rw = m_st.w;
                     const int len = m_rp.y - m_rp.x;
                     if (m_ci >= 0 && s.q != 0.f && len > 0 && len <= GRAM_MAX_ROW) {
                         const ChunkDev &ch = l_desc[m_ci];
@@ -301,12 +301,11 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                     const int ring = (i + 1) & (RING - 1);
                     float t0 = 0.f, lo = 0.f, hi = 0.f;
                     if (r.len > 0) {
-                        const float z = r.zw + part;
                         if (LOSS == 0) {
-                            t0 = (sc.c / r.q) * (1.f - r.y * z);
+                            t0 = (sc.c / r.q) * (r.rw - r.y * part);
                             lo = -r.alpha; hi = 1.f - r.alpha;
                         } else {
-                            t0 = (sc.c / (sc.c + r.q)) * (r.y - r.alpha - z);
+                            t0 = (sc.c / (sc.c + r.q)) * (r.rw - r.alpha - part);
                         }
                     }
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;

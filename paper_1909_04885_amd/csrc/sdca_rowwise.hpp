@@ -7,24 +7,27 @@
 //     hinge   : a' = clip(a + c (1 - y z) / q, 0, 1),  c = lambda n / sigma,  z = x_i . v_k
 //     squared : delta = (y - z - a) / (1 + q / c)
 //     v_k += (delta s / c) x_i,  s = y (hinge) or 1 (squared).
-// The private vector is stored as its difference u_k = v_k - w (zero when the pass starts), and
-// x_i . w comes from the per-row array zw that the gap pass left in the chunk, so z = zw_i + x_i . u_k.
-// Keeping the small difference apart from w keeps fp32 rounding relative to the update, not to w.
+// The private vector is stored as its difference u_k = v_k - w (zero when the pass starts).  The part
+// of a step that depends on w alone is the per-row residual rw that the gap pass left in the chunk
+// (hinge: 1 - y x_i.w, squared: y - x_i.w, formed in double from the double-precision w), so a step
+// needs only x_i . u_k on top of it.  Keeping the small quantities apart from the O(1) ones keeps fp32
+// rounding relative to the update: near convergence y - z - a is a difference of nearly equal numbers.
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
 
 namespace chicle {
 
+// rw: residual at w (see above); xu = x_i . u_k.
 template <int LOSS>
-__device__ __forceinline__ float dual_step(float a, float y, float z, float q, float c)
+__device__ __forceinline__ float dual_step(float a, float y, float rw, float xu, float q, float c)
 {
     if (LOSS == 0) {
-        float an = a + c * (1.0f - y * z) / q;
+        float an = a + c * (rw - y * xu) / q;
         an = fminf(fmaxf(an, 0.0f), 1.0f);
         return an - a;
     }
-    return (y - z - a) / (1.0f + q / c);
+    return (rw - xu - a) / (1.0f + q / c);
 }
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -97,13 +100,13 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
         const float y = st.y;
         const float a = st.alpha;
-        const float zw = st.zw;
+        const float rw = st.rw;
         const int32_t *col = ch.col;
         const float *val = ch.val;
         float part = 0.0f;
         for (int p = b + tid; p < e; p += BLOCK) part += val[p] * v[col[p]];
-        const float z = zw + block_sum<BLOCK>(part, red);
-        const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
+        const float xu = block_sum<BLOCK>(part, red);
+        const float delta = dual_step<LOSS>(a, y, rw, xu, q, sc.c);
         if (tid == 0) ch.st[r].alpha = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
         if (coef != 0.0f)
@@ -154,11 +157,11 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
         const float *x = ch.val + (int64_t)r * d;
         const float y = st.y;
         const float a = st.alpha;
-        const float zw = st.zw;
+        const float rw = st.rw;
         float part = 0.0f;
         for (int p = tid; p < d; p += BLOCK) part += x[p] * v[p];
-        const float z = zw + block_sum<BLOCK>(part, red);
-        const float delta = dual_step<LOSS>(a, y, z, q, sc.c);
+        const float xu = block_sum<BLOCK>(part, red);
+        const float delta = dual_step<LOSS>(a, y, rw, xu, q, sc.c);
         if (tid == 0) ch.st[r].alpha = a + delta;
         const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
         if (coef != 0.0f)
