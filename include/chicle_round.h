@@ -141,7 +141,14 @@ int chicle_set_solver(chicle_ctx *ctx, int32_t kind);
  * An out-of-range perm entry is skipped and reported as EDEVICE by the next synchronising call. */
 int chicle_local_epoch(chicle_ctx *ctx, const int32_t *perm_device);
 
-/* Same with the orders given as a host array (copied to a staging area first). */
+/* Same, and perm_next_device (may be NULL) announces the orders of the following local pass: work for it
+ * that depends on the data and the orders alone (the Gram blocks of the batched solver) is started on a
+ * stream of the library's own, ordered after everything enqueued on the context's stream before this call,
+ * and runs beside this pass.  It is used if the next call passes the same pointer as perm_device with
+ * unchanged contents; otherwise it is discarded (an assign discards it too). */
+int chicle_local_epoch_ahead(chicle_ctx *ctx, const int32_t *perm_device, const int32_t *perm_next_device);
+
+/* Same as chicle_local_epoch with the orders given as a host array (copied to a staging area first). */
 int chicle_local_epoch_host_perm(chicle_ctx *ctx, const int32_t *perm_host);
 
 /* Trainer step (Section 4.1: merge updates, broadcast the model): w <- w + sum_k Delta w_k, then every

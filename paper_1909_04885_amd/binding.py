@@ -24,7 +24,7 @@ SEGMENT = {"local_epoch": 0, "aggregate": 1, "gap": 2, "epoch_gram": 3, "epoch_c
 EXPORTS = [
     "chicle_arena_bytes", "chicle_create", "chicle_load_chunk_csr", "chicle_load_chunk_dense",
     "chicle_balance", "chicle_assign", "chicle_solver_rows", "chicle_set_solver",
-    "chicle_local_epoch", "chicle_local_epoch_host_perm", "chicle_aggregate", "chicle_gap",
+    "chicle_local_epoch", "chicle_local_epoch_ahead", "chicle_local_epoch_host_perm", "chicle_aggregate", "chicle_gap",
     "chicle_get_w", "chicle_set_w", "chicle_get_delta_w", "chicle_get_alpha", "chicle_set_alpha",
     "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
@@ -66,6 +66,7 @@ def load_library():
         "chicle_solver_rows": (ctypes.c_int, [vp, vp]),
         "chicle_set_solver": (ctypes.c_int, [vp, i32]),
         "chicle_local_epoch": (ctypes.c_int, [vp, vp]),
+        "chicle_local_epoch_ahead": (ctypes.c_int, [vp, vp, vp]),
         "chicle_local_epoch_host_perm": (ctypes.c_int, [vp, vp]),
         "chicle_aggregate": (ctypes.c_int, [vp]),
         "chicle_gap": (ctypes.c_int, [vp, ctypes.POINTER(dbl), ctypes.POINTER(dbl), ctypes.POINTER(dbl)]),
@@ -207,11 +208,17 @@ class ChicleRound:
             raise ChicleError(EINVAL, "orders must cover every row once")
         return self._torch.from_numpy(flat).to(self.device)
 
-    def local_epoch(self, perm_device):
-        t = perm_device
+    def _perm_ptr(self, t):
         if t.dtype != self._torch.int32 or not t.is_cuda or not t.is_contiguous() or t.numel() != self.n_total:
             raise ChicleError(EINVAL, "perm must be a contiguous int32 device tensor of n_total entries")
-        self._check(self._L.chicle_local_epoch(self._h, ctypes.c_void_p(t.data_ptr())))
+        return ctypes.c_void_p(t.data_ptr())
+
+    def local_epoch(self, perm_device):
+        self._check(self._L.chicle_local_epoch(self._h, self._perm_ptr(perm_device)))
+
+    def local_epoch_ahead(self, perm_device, perm_next_device=None):
+        nxt = None if perm_next_device is None else self._perm_ptr(perm_next_device)
+        self._check(self._L.chicle_local_epoch_ahead(self._h, self._perm_ptr(perm_device), nxt))
 
     def local_epoch_host_perm(self, perm_host):
         flat = _host(perm_host, np.int32)

@@ -72,7 +72,11 @@ struct chicle_ctx {
     int32_t *rank_of = nullptr, *col_of = nullptr;   // column renumbering tables (device)
     bool renumbered = false;
     int32_t max_row_len = 0;
-    float *tiles = nullptr;
+    float *tiles[2] = {nullptr, nullptr};   // Gram tiles: one set in use by the chain, one being prepared
+    int tile_buf = 0;                       // set the next chain kernel reads
+    hipStream_t side = nullptr;             // stream of Gram kernels prepared ahead
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    const int32_t *ahead_perm = nullptr;    // visiting orders whose tiles are in tiles[1 - tile_buf] (side stream)
     int32_t *tile_solver_dev = nullptr;
     int32_t *row_chunk_dev = nullptr, *chunk_first_dev = nullptr, *list_base_dev = nullptr;
     int64_t max_tiles = 0;
@@ -142,7 +146,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(double) * (size_t)ld);                          // w in double
     s += align_up(sizeof(float) * (size_t)ld * (size_t)max_solvers);     // private vectors
     s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
-    s += align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
+    s += 2 * align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
     s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, row -> chunk
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);               // chunk_first, list_base
@@ -255,8 +259,9 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
     return CHICLE_OK;
 }
 
+// Gram tiles of the given visiting orders into tile set `buf`, on `stream`.
 template <int LOSS>
-int launch_gram(chicle_ctx *c, const int32_t *perm)
+int launch_gram(chicle_ctx *c, const int32_t *perm, int buf, hipStream_t stream)
 {
     const RoundScalars sc = scalars(c);
     if (c->n_tiles > 0) {
@@ -265,22 +270,35 @@ int launch_gram(chicle_ctx *c, const int32_t *perm)
                                        (int)sizeof(GramShared)));
         // each workgroup takes a contiguous run of tiles (neighbouring tiles share half their rows)
         const int grid = std::min(c->n_tiles, 2048);
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(GRAM_THREADS), sizeof(GramShared), c->stream,
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(GRAM_THREADS), sizeof(GramShared), stream,
                            c->chunks_dev, c->solvers_dev, c->row_chunk_dev, c->chunk_first_dev, perm,
-                           c->tile_solver_dev, c->tiles, c->n_tiles, sc.c, c->err_dev);
+                           c->tile_solver_dev, c->tiles[buf], c->n_tiles, sc.c, c->err_dev);
     }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;
 }
 
+// The batched local pass.  Tiles of `perm` come from the set prepared ahead when there is one, else
+// they are computed first on the main stream.  With perm_next, the tiles of the next pass are started
+// on the side stream so that they run beside this pass's chain kernel (which occupies K of the 256
+// compute units); they depend on the data and the orders only.
 template <int LOSS>
-int launch_batched(chicle_ctx *c, const int32_t *perm)
+int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
 {
     const RoundScalars sc = scalars(c);
-    seg_begin(c, CHICLE_SEG_EPOCH_GRAM);
-    int rc = launch_gram<LOSS>(c, perm);
-    seg_end(c, CHICLE_SEG_EPOCH_GRAM);
-    if (rc) return rc;
+    int rc;
+    if (c->ahead_perm != nullptr && c->ahead_perm == perm) {
+        c->tile_buf = 1 - c->tile_buf;
+        HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+    } else {
+        if (c->ahead_perm) HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));   // unused, but let it finish
+        seg_begin(c, CHICLE_SEG_EPOCH_GRAM);
+        rc = launch_gram<LOSS>(c, perm, c->tile_buf, c->stream);
+        seg_end(c, CHICLE_SEG_EPOCH_GRAM);
+        if (rc) return rc;
+    }
+    c->ahead_perm = nullptr;
+    if (perm_next) HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));   // everything enqueued so far
     const int ml = std::max(c->max_list, 1);
     const int n_hot = (int)std::min<int64_t>(HOT_COLS, c->d);
     const size_t sh = sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + sizeof(float) * (size_t)n_hot;
@@ -288,10 +306,31 @@ int launch_batched(chicle_ctx *c, const int32_t *perm)
     HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
     seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
     hipLaunchKernelGGL(kern, dim3(c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
-                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles, c->u, c->ld_v, ml, n_hot, sc,
-                       c->err_dev);
+                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u, c->ld_v, ml,
+                       n_hot, sc, c->err_dev);
     seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
     HIP_TRY(c, hipGetLastError());
+    if (perm_next) {
+        // the other tile set was last read by the previous pass's chain kernel, which precedes ev_fork
+        HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        if (c->profiling) (void)hipEventRecord(c->seg[CHICLE_SEG_EPOCH_GRAM].start, c->side);
+        rc = launch_gram<LOSS>(c, perm_next, 1 - c->tile_buf, c->side);
+        if (c->profiling) {
+            (void)hipEventRecord(c->seg[CHICLE_SEG_EPOCH_GRAM].stop, c->side);
+            c->seg[CHICLE_SEG_EPOCH_GRAM].recorded = true;
+        }
+        if (rc) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
+        c->ahead_perm = perm_next;
+    }
+    return CHICLE_OK;
+}
+
+// Work prepared ahead refers to the solver tables: finish it before they change.
+int drop_ahead(chicle_ctx *c)
+{
+    if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
+    c->ahead_perm = nullptr;
     return CHICLE_OK;
 }
 
@@ -446,7 +485,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->u = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
     c->rank_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
     c->col_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
-    c->tiles = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
+    c->tiles[0] = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
+    c->tiles[1] = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
     c->tile_solver_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->max_tiles);
     c->perm_stage = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
     c->row_chunk_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
@@ -470,6 +510,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
               hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess;
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
     if (!ok) { chicle_destroy(c); return CHICLE_EDEVICE; }
     *out = c;
     return CHICLE_OK;
@@ -628,6 +671,7 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     if (!chunk_to_solver) return fail(c, CHICLE_EINVAL, "table is NULL");
     if (c->n_loaded != c->n_chunks) return fail(c, CHICLE_EINVAL, "%d of %d chunks loaded", c->n_loaded, c->n_chunks);
     if (c->rows_loaded != c->n_total) return fail(c, CHICLE_EINVAL, "chunks hold %lld rows, n_total is %lld", (long long)c->rows_loaded, (long long)c->n_total);
+    { const int rc0 = drop_ahead(c); if (rc0) return rc0; }
     std::vector<int32_t> count(K, 0);
     for (int32_t i = 0; i < c->n_chunks; ++i) {
         if (chunk_to_solver[i] < 0 || chunk_to_solver[i] >= K)
@@ -714,6 +758,11 @@ int chicle_set_solver(chicle_ctx *c, int32_t kind)
 
 int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
 {
+    return chicle_local_epoch_ahead(c, perm_device, nullptr);
+}
+
+int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const int32_t *perm_next_device)
+{
     if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
     if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
@@ -730,7 +779,8 @@ int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
     if (!c->zw_valid) rc = run_row_pass(c, nullptr);     // x_i . w for the current w
     if (rc == CHICLE_OK) {
         if (batched) {
-            rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device) : launch_batched<1>(c, perm_device);
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device, perm_next_device)
+                                              : launch_batched<1>(c, perm_device, perm_next_device);
         } else {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device) : launch_rowwise<1>(c, perm_device);
@@ -904,12 +954,15 @@ int chicle_debug_gram(chicle_ctx *c, const int32_t *perm_device, float *tiles_ou
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, "needs an assignment and no pending epoch");
     if (!batched_eligible(c)) return fail(c, CHICLE_EINVAL, "batched solver not available for this data");
     if (n_tiles_out) *n_tiles_out = c->n_tiles;
-    const int rc = c->loss == CHICLE_LOSS_HINGE ? launch_gram<0>(c, perm_device) : launch_gram<1>(c, perm_device);
+    int rc = drop_ahead(c);
+    if (rc) return rc;
+    rc = c->loss == CHICLE_LOSS_HINGE ? launch_gram<0>(c, perm_device, c->tile_buf, c->stream)
+                                      : launch_gram<1>(c, perm_device, c->tile_buf, c->stream);
     if (rc) return rc;
     if (tiles_out) {
         const int64_t want = (int64_t)c->n_tiles * TILE_FLOATS;
         if (capacity_floats < want) return fail(c, CHICLE_EINVAL, "need room for %lld floats", (long long)want);
-        HIP_TRY(c, hipMemcpyAsync(tiles_out, c->tiles, sizeof(float) * (size_t)want, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(tiles_out, c->tiles[c->tile_buf], sizeof(float) * (size_t)want, hipMemcpyDeviceToHost, c->stream));
     }
     return check_deferred(c);
 }
@@ -919,7 +972,11 @@ const char *chicle_last_error(chicle_ctx *c) { return c ? c->err.c_str() : "null
 void chicle_destroy(chicle_ctx *c)
 {
     if (!c) return;
+    if (c->side) (void)hipStreamSynchronize(c->side);
     (void)hipStreamSynchronize(c->stream);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     for (int s = 0; s < CHICLE_SEG_COUNT; ++s) {
         if (c->seg[s].start) (void)hipEventDestroy(c->seg[s].start);
         if (c->seg[s].stop) (void)hipEventDestroy(c->seg[s].stop);

@@ -27,7 +27,7 @@ def rel_l2(got: np.ndarray, ref: np.ndarray, floor: float) -> float:
 
 
 def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sample_solvers=None,
-                 check_alpha_every=0, log=None):
+                 check_alpha_every=0, log=None, ahead=False):
     """Returns a dict of per-round records; raises AssertionError on the first violation."""
     o = oracle_mod.OracleCoCoA.from_problem(p)
     maxK = max(k for _, k in cfg["schedule"])
@@ -37,6 +37,7 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
     K = None
     rec = []
     loads = p.chunk_nnz()
+    next_dev = None      # visiting orders of round r already in HBM (announced during round r - 1)
     for r in range(rounds):
         Kr = k_for_round(cfg, r)
         if Kr != K:
@@ -55,7 +56,15 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
                 for c, a in enumerate(alpha_before):
                     assert np.array_equal(a, g.get_alpha(c))
         perms = round_permutations(cfg["seed"], r, o.rows_per_solver())
-        g.local_epoch(g.upload_perm(perms))
+        if not ahead:
+            g.local_epoch(g.upload_perm(perms))
+        else:
+            # announce the next round's orders unless the schedule reassigns chunks before it
+            cur_dev = next_dev if next_dev is not None else g.upload_perm(perms)
+            next_dev = None
+            if r + 1 < rounds and k_for_round(cfg, r + 1) == K:
+                next_dev = g.upload_perm(round_permutations(cfg["seed"], r + 1, o.rows_per_solver()))
+            g.local_epoch_ahead(cur_dev, next_dev)
         wnorm = float(np.linalg.norm(o.w))
         worst = [0.0]
         which = set(range(K)) if sample_solvers is None else {s % K for s in sample_solvers}

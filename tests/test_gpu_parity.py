@@ -26,17 +26,19 @@ def mods(oracle_mod):
     return oracle_mod, binding
 
 
-MINI_CASES = [("dense_hinge", "rowwise"), ("dense_ridge", "rowwise"), ("sparse_zipf", "rowwise"),
-              ("sparse_longrow", "rowwise"), ("elastic", "rowwise"), ("sparse_zipf", "batched"),
-              ("elastic", "batched")]
+MINI_CASES = [("dense_hinge", "rowwise", False), ("dense_ridge", "rowwise", False),
+              ("sparse_zipf", "rowwise", False), ("sparse_longrow", "rowwise", False),
+              ("elastic", "rowwise", False), ("sparse_zipf", "batched", False),
+              ("elastic", "batched", False), ("sparse_zipf", "batched", True), ("elastic", "batched", True),
+              ("dense_ridge", "auto", True)]
 
 
-@pytest.mark.parametrize("name,solver", MINI_CASES)
-def test_mini_all_solvers_every_round(mods, name, solver):
+@pytest.mark.parametrize("name,solver,ahead", MINI_CASES)
+def test_mini_all_solvers_every_round(mods, name, solver, ahead):
     oracle_mod, binding = mods
     cfg, p = cached_problem(name, "mini")
-    print("\ncase", name, "mini", solver, "n=%d d=%d" % (p.n, p.d), flush=True)
-    run_lockstep(cfg, p, oracle_mod, binding, solver=solver, check_alpha_every=1, log=_log)
+    print("\ncase", name, "mini", solver, "ahead" if ahead else "", "n=%d d=%d" % (p.n, p.d), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, solver=solver, check_alpha_every=1, log=_log, ahead=ahead)
 
 
 @pytest.mark.parametrize("name", ["dense_hinge", "dense_ridge"])
@@ -53,7 +55,7 @@ def test_full_sparse_zipf(mods, name):
     cfg, p = cached_problem("sparse_zipf", "full")
     cfg = get_config(name, "full")
     print("\ncase", name, "full n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
-    run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 3, 7, 31], log=_log)
+    run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 3, 7, 31], log=_log, ahead=True)
 
 
 def test_full_sparse_longrow(mods):
