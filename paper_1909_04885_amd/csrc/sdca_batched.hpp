@@ -27,7 +27,7 @@ constexpr int TILE_W = 2 * BATCH;            // T rows: previous block (cross pa
 constexpr int TILE_FLOATS = BATCH * TILE_W;  // layout [jp][i]: jp in [0,128), i in [0,64)
 constexpr int GRAM_MAX_ROW = 48;             // longest sparse row the batched solver accepts
 constexpr int LPR = 8;                       // helper lanes per row
-constexpr int ENT = GRAM_MAX_ROW / LPR;      // entries per helper lane (6: one 16-byte and one 8-byte load)
+constexpr int ENT = GRAM_MAX_ROW / LPR;      // entries per helper lane
 constexpr int HELPER_WAVES = BATCH * LPR / 64;
 constexpr int SERVICE_WAVES = 2;              // row resolution and tile staging
 constexpr int BATCHED_THREADS = 64 + BATCH * LPR + 64 * SERVICE_WAVES;
@@ -244,15 +244,14 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
             //    entries beyond the row's length are masked when the set moves on)
             if (i + 2 >= 0 && i + 2 < nb) {
                 const RowSlot &r = sh.rows[(i + 2) & (RING - 1)][rho];
-                const int32_t *cp = r.col + sub * ENT;
-                const float *vp = r.val + sub * ENT;
+                // lane sub takes positions sub, sub + 8, ...: the row is sorted by column popularity, so
+                // for one e the eight lanes of a row hold neighbouring ranks and the split "popular
+                // column in LDS / other column in HBM" is nearly uniform over the wavefront
+                const int32_t *cp = r.col + sub;
+                const float *vp = r.val + sub;
                 in_len = r.len;
-                const int4_a4 c4 = gld4(cp);
-                const int2_a4 c2 = gld2(cp + 4);
-                const float4_a4 v4 = gld4(vp);
-                const float2_a4 v2 = gld2(vp + 4);
-                in_c[0] = c4.x; in_c[1] = c4.y; in_c[2] = c4.z; in_c[3] = c4.w; in_c[4] = c2.x; in_c[5] = c2.y;
-                in_v[0] = v4.x; in_v[1] = v4.y; in_v[2] = v4.z; in_v[3] = v4.w; in_v[4] = v2.x; in_v[5] = v2.y;
+#pragma unroll
+                for (int e = 0; e < ENT; ++e) { in_c[e] = gld(cp + e * LPR); in_v[e] = gld(vp + e * LPR); }
             } else {
                 in_len = 0;
             }
@@ -281,19 +280,24 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
             // 7. gather block i + 1 against the private vector (blocks <= i - 1 applied)
             if (i + 1 >= 0 && i + 1 < nb) {
                 const RowSlot &r = sh.rows[(i + 1) & (RING - 1)][rho];
-                // Unconditional loads (masked entries hold column 0 with value 0), all issued before
-                // the first use, so that one round trip covers the whole gather.
+                // All loads are issued before the first use so that one round trip covers the gather;
+                // cold_v and hot_v are separate so that neither branch has to wait for its own load.
+                // Masked entries hold value 0 and are skipped.
                 float cold_v[ENT], hot_v[ENT];
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) {
-                    const bool cold = g_c[e] >= n_hot;
-                    cold_v[e] = __hip_atomic_load(u + (cold ? g_c[e] : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    hot_v[e] = hot[cold ? 0 : g_c[e]];
+                    cold_v[e] = 0.f;
+                    if (g_v[e] != 0.f && g_c[e] >= n_hot)
+                        cold_v[e] = __hip_atomic_load(u + g_c[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int e = 0; e < ENT; ++e) {
+                    hot_v[e] = 0.f;
+                    if (g_v[e] != 0.f && g_c[e] < n_hot) hot_v[e] = hot[g_c[e]];
                 }
                 float part = 0.f;
 #pragma unroll
-                for (int e = 0; e < ENT; ++e)
-                    part += g_v[e] * (g_c[e] >= n_hot ? cold_v[e] : hot_v[e]);
+                for (int e = 0; e < ENT; ++e) part += g_v[e] * (cold_v[e] + hot_v[e]);
                 part += __shfl_xor(part, 1, 64);
                 part += __shfl_xor(part, 2, 64);
                 part += __shfl_xor(part, 4, 64);
@@ -316,7 +320,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
             for (int e = 0; e < ENT; ++e) {
                 s_c[e] = c_c[e]; s_v[e] = c_v[e];
                 c_c[e] = g_c[e]; c_v[e] = g_v[e];
-                const bool live = sub * ENT + e < in_len;
+                const bool live = sub + e * LPR < in_len;
                 g_c[e] = live ? in_c[e] : 0;
                 g_v[e] = live ? in_v[e] : 0.f;
             }
