@@ -53,7 +53,8 @@ struct chicle_ctx {
     int64_t ld_v = 0;
     double lambda = 0;
     int32_t n_chunks = 0, max_solvers = 0;
-    bool dense = false;
+    bool dense = false;        // chunks stored as dense row-major matrices
+    bool api_dense = false;    // chunks arrive through chicle_load_chunk_dense
     int64_t total_entries = 0;
     char *arena = nullptr;
     size_t arena_bytes = 0, used = 0;
@@ -222,6 +223,11 @@ RoundScalars scalars(const chicle_ctx *c)
     s.K = c->K;
     return s;
 }
+
+// Dense rows short enough for the batched solver are stored with explicit column ids (row-major,
+// columns 0 .. d-1): twice the bytes of the dense form, and every machinery for short sparse rows
+// applies to them unchanged.
+bool dense_as_csr(int32_t d) { return d <= GRAM_MAX_ROW; }
 
 bool batched_eligible(const chicle_ctx *c)
 {
@@ -443,7 +449,7 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
     size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
     const size_t per_chunk_slack = 8 * ALIGN + 2 * sizeof(float) * ENTRY_SLACK;
-    if (dense)
+    if (dense && !dense_as_csr(d))
         s += sizeof(float) * (size_t)total_entries + 4 * sizeof(float) * (size_t)n_total;
     else
         s += (sizeof(int32_t) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
@@ -467,7 +473,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     chicle_ctx *c = new (std::nothrow) chicle_ctx();
     if (!c) return CHICLE_ENOMEM;
     c->loss = loss; c->n_total = n_total; c->d = d; c->ld_v = pad_d(d); c->lambda = lambda;
-    c->n_chunks = n_chunks; c->max_solvers = max_solvers; c->dense = dense != 0;
+    c->n_chunks = n_chunks; c->max_solvers = max_solvers;
+    c->api_dense = dense != 0;
+    c->dense = c->api_dense && !dense_as_csr(d);
     c->total_entries = total_entries;
     c->arena = (char *)device_arena; c->arena_bytes = arena_bytes;
     c->stream = (hipStream_t)hip_stream;
@@ -571,11 +579,20 @@ static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const floa
     return CHICLE_OK;
 }
 
+static int load_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
+                    const int32_t *col, const float *val, const float *y, const float *alpha0);
+
 int chicle_load_chunk_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
                           const int32_t *col, const float *val, const float *y, const float *alpha0)
 {
     if (!c) return CHICLE_EINVAL;
-    if (c->dense) return fail(c, CHICLE_EINVAL, "context holds dense chunks");
+    if (c->api_dense) return fail(c, CHICLE_EINVAL, "context holds dense chunks");
+    return load_csr(c, chunk_id, n_rows, row_ptr, col, val, y, alpha0);
+}
+
+static int load_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
+                    const int32_t *col, const float *val, const float *y, const float *alpha0)
+{
     if (!row_ptr || n_rows <= 0) return fail(c, CHICLE_EINVAL, "chunk %d: row_ptr NULL or no rows", chunk_id);
     if (row_ptr[0] != 0) return fail(c, CHICLE_EINVAL, "chunk %d: row_ptr[0] must be 0", chunk_id);
     for (int32_t r = 0; r < n_rows; ++r)
@@ -621,9 +638,16 @@ int chicle_load_chunk_dense(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, con
                             const float *y, const float *alpha0)
 {
     if (!c) return CHICLE_EINVAL;
-    if (!c->dense) return fail(c, CHICLE_EINVAL, "context holds CSR chunks");
+    if (!c->api_dense) return fail(c, CHICLE_EINVAL, "context holds CSR chunks");
     if (!X || n_rows <= 0) return fail(c, CHICLE_EINVAL, "chunk %d: X NULL or no rows", chunk_id);
     const int64_t entries = (int64_t)n_rows * c->d;
+    if (!c->dense) {                       // short dense rows: explicit column ids
+        if (entries > INT32_MAX) return fail(c, CHICLE_EINVAL, "chunk %d too large", chunk_id);
+        std::vector<int32_t> rp(n_rows + 1), cols((size_t)entries);
+        for (int32_t r = 0; r <= n_rows; ++r) rp[r] = r * c->d;
+        for (int64_t p = 0; p < entries; ++p) cols[p] = (int32_t)(p % c->d);
+        return load_csr(c, chunk_id, n_rows, rp.data(), cols.data(), X, y, alpha0);
+    }
     int rc = load_common(c, chunk_id, n_rows, entries);
     if (rc) return rc;
     rc = check_state_arrays(c, chunk_id, n_rows, y, alpha0);
