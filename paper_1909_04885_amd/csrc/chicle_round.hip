@@ -27,7 +27,7 @@ namespace {
 constexpr size_t ALIGN = 256;
 constexpr int GAP_PARTS = 4096;        // workgroups (and partial sums) of the gap row kernels
 constexpr int WSQ_PARTS = 512;
-constexpr int MAX_LIST_LDS = 4096;     // chunks one solver may own (its lists are staged in LDS)
+constexpr int MAX_LIST_LDS = 768;      // chunks one solver may own (their descriptors are staged in LDS)
 constexpr int DENSE_V_LDS_MAX_D = 8192;
 constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
@@ -252,14 +252,16 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
                                perm, c->u, c->ld_v, (int)c->d, std::max(c->max_list, 1), sc, c->err_dev);
     } else {
         const double avg = c->n_total ? (double)c->total_entries / (double)c->n_total : 0.0;
+        const int ml = std::max(c->max_list, 1);
+        const size_t sh = (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml;
         if (avg <= 96.0)
-            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64>), dim3(c->K), dim3(64), list_bytes, c->stream,
+            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64, 2>), dim3(c->K), dim3(64), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->u, c->ld_v, sc, c->err_dev);
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev);
         else
-            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 256>), dim3(c->K), dim3(256), list_bytes, c->stream,
+            hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 512, 4>), dim3(c->K), dim3(512), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->u, c->ld_v, sc, c->err_dev);
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev);
     }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;

@@ -18,6 +18,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
+#include "mem.hpp"
 #include "sdca_rowwise.hpp"
 
 namespace chicle {
@@ -33,23 +34,6 @@ constexpr int SERVICE_WAVES = 2;              // row resolution and tile staging
 constexpr int BATCHED_THREADS = 64 + BATCH * LPR + 64 * SERVICE_WAVES;
 constexpr int RING = 8;
 constexpr int HOT_COLS = 12288;               // head of the private vector kept in LDS (popular columns)
-
-// Loads and stores through pointers that were parked in LDS: the compiler no longer knows that they
-// point to HBM and would emit flat accesses, whose completion is counted together with LDS traffic.
-#define CHICLE_GLOBAL __attribute__((address_space(1)))
-typedef int int2_a4 __attribute__((ext_vector_type(2), aligned(4)));
-typedef int int4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-typedef float float2_a4 __attribute__((ext_vector_type(2), aligned(4)));
-typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-__device__ __forceinline__ int gld(const int32_t *p) { return *(const CHICLE_GLOBAL int32_t *)p; }
-__device__ __forceinline__ float gld(const float *p) { return *(const CHICLE_GLOBAL float *)p; }
-__device__ __forceinline__ int2_a4 gld2(const int32_t *p) { return *(const CHICLE_GLOBAL int2_a4 *)p; }
-__device__ __forceinline__ int4_a4 gld4(const int32_t *p) { return *(const CHICLE_GLOBAL int4_a4 *)p; }
-__device__ __forceinline__ float2_a4 gld2(const float *p) { return *(const CHICLE_GLOBAL float2_a4 *)p; }
-__device__ __forceinline__ float4_a4 gld4(const float *p) { return *(const CHICLE_GLOBAL float4_a4 *)p; }
-typedef float float4_v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4_v gld_state(const RowState *p) { return *(const CHICLE_GLOBAL float4_v *)p; }
-__device__ __forceinline__ void gst(float *p, float x) { *(CHICLE_GLOBAL float *)p = x; }
 
 // What the helpers know about one row of a block.
 struct RowSlot {

@@ -15,6 +15,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
+#include "mem.hpp"
 
 namespace chicle {
 
@@ -64,54 +65,122 @@ __device__ __forceinline__ int find_chunk(const int *prefix, int n, int lr)
     return lo;
 }
 
-// Sparse rows.  Dynamic LDS: 2 * max_list ints (chunk ids, then local-row prefixes).
-template <int LOSS, int BLOCK>
+// What a step needs to know about its row; len = 0 marks a row to skip.
+struct RowMeta {
+    const int32_t *col;
+    const float *val;
+    RowState *st;
+    int len;
+    float y, alpha, q, rw;
+};
+
+// Sparse rows of any length.  The step itself is gather - reduce - step - scatter; everything that does
+// not depend on the private vector is fetched ahead by a small software pipeline so that a step costs
+// one trip to memory (the gather) instead of five dependent ones:
+//     step t issues   the order entry of row t+4, the chunk lookup and state loads of row t+3,
+//     publishes       the resolved row t+2 in LDS (thread 0 does these three),
+//     loads           the first EPT * BLOCK entries of row t+1 into registers (all threads),
+//     computes        row t.
+// The scatter uses atomic adds that are not waited for: accesses of one compute unit to one address
+// are served in order, and the gathers read past the vector cache (ld_l2).
+// Dynamic LDS: max_list chunk descriptors, then max_list local-row prefixes.
+template <int LOSS, int BLOCK, int EPT>
 __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
-    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, RoundScalars sc, int *err)
+    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, int max_list, RoundScalars sc, int *err)
 {
-    extern __shared__ int lists[];
+    extern __shared__ __align__(16) unsigned char rw_smem[];
     __shared__ float red[BLOCK / 64];
+    __shared__ RowMeta ring[4];
     const SolverDev S = solvers[blockIdx.x];
-    int *l_chunk = lists;
-    int *l_prefix = lists + S.n_chunks;
-    for (int i = threadIdx.x; i < S.n_chunks; i += BLOCK) {
-        l_chunk[i] = solver_chunks[S.list_begin + i];
+    ChunkDev *l_desc = reinterpret_cast<ChunkDev *>(rw_smem);
+    int *l_prefix = reinterpret_cast<int *>(l_desc + max_list);
+    const int tid = threadIdx.x;
+    for (int i = tid; i < S.n_chunks; i += BLOCK) {
+        l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
     __syncthreads();
-    float *v = u_all + (int64_t)blockIdx.x * ld_v;
+    float *u = u_all + (int64_t)blockIdx.x * ld_v;
     const int32_t *pk = perm + S.perm_off;
-    const int tid = threadIdx.x;
+    const int n = S.n_rows;
 
-    for (int t = 0; t < S.n_rows; ++t) {
-        const int lr = pk[t];
-        if ((unsigned)lr >= (unsigned)S.n_rows) {
-            if (tid == 0) atomicOr(err, ERR_PERM_RANGE);
-            continue;
+    // thread 0: rows being resolved
+    int p_val = -1;                       // order entry of the row resolved next step
+    int m_ci = -1, m_r = 0;               // row whose state loads are in flight
+    int2_a4 m_rp = {0, 0};
+    float4_v m_st = {0.f, 0.f, 0.f, 0.f};
+    // all threads: entries of the current and of the next row
+    int c_c[EPT], n_c[EPT];
+    float c_v[EPT], n_v[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) { c_c[e] = n_c[e] = 0; c_v[e] = n_v[e] = 0.f; }
+
+    for (int t = -4; t < n; ++t) {
+        if (tid == 0) {
+            // publish row t + 2 (state loads issued last step)
+            if (t + 2 >= 0 && t + 2 < n) {
+                RowMeta m;
+                m.col = nullptr; m.val = nullptr; m.st = nullptr; m.len = 0;
+                m.y = m_st.x; m.alpha = m_st.y; m.q = m_st.z; m.rw = m_st.w;
+                const int len = m_rp.y - m_rp.x;
+                if (m_ci >= 0 && m.q != 0.f && len > 0) {
+                    const ChunkDev &ch = l_desc[m_ci];
+                    m.col = ch.col + m_rp.x; m.val = ch.val + m_rp.x; m.st = ch.st + m_r; m.len = len;
+                }
+                ring[(t + 2) & 3] = m;
+            }
+            // state loads of row t + 3
+            m_ci = -1;
+            if (t + 3 >= 0 && t + 3 < n) {
+                if ((unsigned)p_val >= (unsigned)n) {
+                    atomicOr(err, ERR_PERM_RANGE);
+                } else {
+                    m_ci = find_chunk(l_prefix, S.n_chunks, p_val);
+                    m_r = p_val - l_prefix[m_ci];
+                    const ChunkDev &ch = l_desc[m_ci];
+                    m_rp = gld2(ch.row_ptr + m_r);
+                    m_st = gld_state(ch.st + m_r);
+                }
+            }
+            // order entry of row t + 4
+            p_val = (t + 4 >= 0 && t + 4 < n) ? pk[t + 4] : -1;
         }
-        const int j = find_chunk(l_prefix, S.n_chunks, lr);
-        const ChunkDev &ch = chunks[l_chunk[j]];
-        const int r = lr - l_prefix[j];
-        const RowState st = ch.st[r];
-        const float q = st.q;
-        if (q == 0.0f) continue;
-        const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-        const float y = st.y;
-        const float a = st.alpha;
-        const float rw = st.rw;
-        const int32_t *col = ch.col;
-        const float *val = ch.val;
-        float part = 0.0f;
-        for (int p = b + tid; p < e; p += BLOCK) part += val[p] * v[col[p]];
-        const float xu = block_sum<BLOCK>(part, red);
-        const float delta = dual_step<LOSS>(a, y, rw, xu, q, sc.c);
-        if (tid == 0) ch.st[r].alpha = a + delta;
-        const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
-        if (coef != 0.0f)
-            for (int p = b + tid; p < e; p += BLOCK) v[col[p]] += coef * val[p];
-        __syncthreads();   // the next step's gather must see this scatter
+        // entries of row t + 1 (published last step)
+        if (t + 1 >= 0 && t + 1 < n) {
+            const RowMeta &m = ring[(t + 1) & 3];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const int p = tid + e * BLOCK;
+                n_c[e] = 0; n_v[e] = 0.f;
+                if (p < m.len) { n_c[e] = gld(m.col + p); n_v[e] = gld(m.val + p); }
+            }
+        }
+        if (t >= 0) {
+            const RowMeta m = ring[t & 3];
+            if (m.len > 0) {                                    // uniform over the workgroup
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPT; ++e)
+                    if (tid + e * BLOCK < m.len) part += c_v[e] * ld_l2(u + c_c[e]);
+                for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK) part += gld(m.val + p) * ld_l2(u + gld(m.col + p));
+                const float xu = block_sum<BLOCK>(part, red);
+                const float delta = dual_step<LOSS>(m.alpha, m.y, m.rw, xu, m.q, sc.c);
+                if (tid == 0) gst(&m.st->alpha, m.alpha + delta);
+                const float coef = delta * (LOSS == 0 ? m.y : 1.0f) * sc.inv_c;
+                if (coef != 0.0f) {
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e)
+                        if (tid + e * BLOCK < m.len) unsafeAtomicAdd(u + c_c[e], coef * c_v[e]);
+                    for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK)
+                        unsafeAtomicAdd(u + gld(m.col + p), coef * gld(m.val + p));
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) { c_c[e] = n_c[e]; c_v[e] = n_v[e]; }
+        __syncthreads();   // ring slots written this step are read next step; orders scatter before gather
     }
 }
 
