@@ -82,9 +82,8 @@ __device__ __forceinline__ void block_sum2_store(double a, double b, double *out
 // for the next local pass (hinge: 1 - y z, squared: y - z with z = x_i . w).  WT is the type the dot
 // product is gathered and accumulated in: double for the squared loss, whose steps cancel y - z - alpha
 // down to the size of the update near convergence; float for hinge.
-// LPR lanes cooperate on one row (LPR divides 64).  Work items are blocks of 256/LPR rows of one chunk;
-// item_prefix[c] = first item of chunk c.  Each workgroup writes one partial (loss sum, conjugate sum)
-// in double.
+// LPR lanes cooperate on one row (LPR divides 64).  Each workgroup writes one partial (loss sum,
+// conjugate sum) in double.
 //   hinge   : loss = max(0, 1 - y z),   conj = loss^*(-a) = -a
 //   squared : loss = (z - y)^2 / 2,     conj = a^2/2 - a y
 template <int LOSS, typename WT>
@@ -104,61 +103,71 @@ __device__ __forceinline__ void gap_row_terms(RowState *st, WT z, double &s_loss
     }
 }
 
+// Grid: (workgroups per chunk, chunks).  Every group of LPR lanes walks rows of its chunk with a fixed
+// stride and keeps two rows in flight.  Partial sums are indexed by the linear workgroup id.
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__ chunks,
-                                                    const int32_t *__restrict__ item_prefix,
-                                                    int n_chunks, int total_items,
                                                     const WT *__restrict__ w,
                                                     double *part_loss, double *part_conj)
 {
-    constexpr int ROWS = 256 / LPR;
+    constexpr int GROUPS = 256 / LPR;
     const int sub = threadIdx.x % LPR;
-    const int rloc = threadIdx.x / LPR;
+    const int grp = threadIdx.x / LPR;
+    const ChunkDev &ch = chunks[blockIdx.y];
+    const int n_rows = ch.n_rows;
+    const int32_t *__restrict__ rp = ch.row_ptr;
+    const int32_t *__restrict__ col = ch.col;
+    const float *__restrict__ val = ch.val;
+    const int stride = gridDim.x * GROUPS;
     double s_loss = 0.0, s_conj = 0.0;
-    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const int c = find_chunk(item_prefix, n_chunks, item);
-        const ChunkDev &ch = chunks[c];
-        const int r = (item - item_prefix[c]) * ROWS + rloc;
-        WT z = 0;
-        const bool live = r < ch.n_rows;
-        if (live) {
-            const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-            for (int p = b + sub; p < e; p += LPR) z += (WT)ch.val[p] * w[ch.col[p]];
+    for (int r0 = blockIdx.x * GROUPS + grp; r0 < n_rows; r0 += 2 * stride) {
+        const int r1 = r0 + stride;
+        const bool two = r1 < n_rows;
+        const int b0 = rp[r0], e0 = rp[r0 + 1];
+        const int b1 = two ? rp[r1] : 0, e1 = two ? rp[r1 + 1] : 0;
+        WT z0 = 0, z1 = 0;
+        int p0 = b0 + sub, p1 = b1 + sub;
+        while (p0 < e0 || p1 < e1) {           // both rows advance together: their loads overlap
+            int c0 = 0, c1 = 0;
+            float v0 = 0.f, v1 = 0.f;
+            if (p0 < e0) { c0 = col[p0]; v0 = val[p0]; }
+            if (p1 < e1) { c1 = col[p1]; v1 = val[p1]; }
+            z0 += (WT)v0 * w[c0];
+            z1 += (WT)v1 * w[c1];
+            p0 += LPR; p1 += LPR;
         }
 #pragma unroll
-        for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
-        if (live && sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
+        for (int o = LPR / 2; o > 0; o >>= 1) { z0 += __shfl_xor(z0, o, 64); z1 += __shfl_xor(z1, o, 64); }
+        if (sub == 0) {
+            gap_row_terms<LOSS, WT>(ch.st + r0, z0, s_loss, s_conj);
+            if (two) gap_row_terms<LOSS, WT>(ch.st + r1, z1, s_loss, s_conj);
+        }
     }
-    block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
+    const int part = blockIdx.y * gridDim.x + blockIdx.x;
+    block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);
 }
 
-// Dense rows: LPR lanes per row, strided over the d columns.
+// Dense rows: LPR lanes per row, strided over the d columns.  Same grid as the sparse kernel.
 template <int LOSS, int LPR, typename WT>
-__global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks,
-                                                      const int32_t *__restrict__ item_prefix,
-                                                      int n_chunks, int total_items, int d,
+__global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks, int d,
                                                       const WT *__restrict__ w,
                                                       double *part_loss, double *part_conj)
 {
-    constexpr int ROWS = 256 / LPR;
+    constexpr int GROUPS = 256 / LPR;
     const int sub = threadIdx.x % LPR;
-    const int rloc = threadIdx.x / LPR;
+    const int grp = threadIdx.x / LPR;
+    const ChunkDev &ch = chunks[blockIdx.y];
     double s_loss = 0.0, s_conj = 0.0;
-    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const int c = find_chunk(item_prefix, n_chunks, item);
-        const ChunkDev &ch = chunks[c];
-        const int r = (item - item_prefix[c]) * ROWS + rloc;
+    for (int r = blockIdx.x * GROUPS + grp; r < ch.n_rows; r += gridDim.x * GROUPS) {
+        const float *x = ch.val + (int64_t)r * d;
         WT z = 0;
-        const bool live = r < ch.n_rows;
-        if (live) {
-            const float *x = ch.val + (int64_t)r * d;
-            for (int p = sub; p < d; p += LPR) z += (WT)x[p] * w[p];
-        }
+        for (int p = sub; p < d; p += LPR) z += (WT)x[p] * w[p];
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
-        if (live && sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
+        if (sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
     }
-    block_sum2_store(s_loss, s_conj, &part_loss[blockIdx.x], &part_conj[blockIdx.x]);
+    const int part = blockIdx.y * gridDim.x + blockIdx.x;
+    block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);
 }
 
 // |w|^2 partials in double.

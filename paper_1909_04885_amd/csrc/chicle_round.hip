@@ -25,7 +25,7 @@ using namespace chicle;
 namespace {
 
 constexpr size_t ALIGN = 256;
-constexpr int GAP_PARTS = 4096;        // workgroups (and partial sums) of the gap row kernels
+constexpr int GAP_PARTS = 8192;        // workgroups (and partial sums) of the gap row kernels, at least
 constexpr int WSQ_PARTS = 512;
 constexpr int MAX_LIST_LDS = 768;      // chunks one solver may own (their descriptors are staged in LDS)
 constexpr int DENSE_V_LDS_MAX_D = 8192;
@@ -98,6 +98,7 @@ struct chicle_ctx {
     std::vector<SolverDev> solvers;
     int max_list = 0;
     int gap_lpr = 64, gap_items = 0;
+    int gap_parts = 0;         // length of the partial-sum arrays of the gap row kernels
 
     bool profiling = false;
     Seg seg[CHICLE_SEG_COUNT];
@@ -151,7 +152,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, row -> chunk
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);               // chunk_first, list_base
-    s += 2 * align_up(sizeof(double) * GAP_PARTS) + 2 * align_up(sizeof(double) * WSQ_PARTS);
+    s += 2 * align_up(sizeof(double) * (size_t)std::max(GAP_PARTS, 2 * n_chunks)) + 2 * align_up(sizeof(double) * WSQ_PARTS);
     s += align_up(sizeof(double) * 4);
     s += align_up(sizeof(int));
     return s;
@@ -343,15 +344,15 @@ int drop_ahead(chicle_ctx *c)
 }
 
 template <int LOSS, int LPRG, typename WT>
-void launch_gap_rows_t(chicle_ctx *c, int grid, const WT *w)
+void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w)
 {
+    const dim3 grid(grid_x, c->n_chunks);
     if (c->dense)
-        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
-                           c->item_prefix_dev, c->n_chunks, c->gap_items, (int)c->d, w, c->part_loss,
-                           c->part_conj);
+        hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev,
+                           (int)c->d, w, c->part_loss, c->part_conj);
     else
-        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), dim3(grid), dim3(256), 0, c->stream, c->chunks_dev,
-                           c->item_prefix_dev, c->n_chunks, c->gap_items, w, c->part_loss, c->part_conj);
+        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev, w,
+                           c->part_loss, c->part_conj);
 }
 
 // Squared loss: dot products in double against the double w (its steps cancel y - z - alpha down to the
@@ -378,11 +379,16 @@ void launch_gap_lpr(chicle_ctx *c, int grid)
 // The row pass of the gap: z_i = x_i . w into the chunks, loss and conjugate partial sums.
 int run_row_pass(chicle_ctx *c, int *grid_out)
 {
-    const int grid = std::max(1, std::min(c->gap_items, GAP_PARTS));
-    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, grid); else launch_gap_lpr<1>(c, grid);
+    // workgroups per chunk: enough to fill the chip several times over, within the partial-sum arrays
+    int max_rows = 1;
+    for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
+    const int rows_per_wg = 2 * (256 / c->gap_lpr);
+    int gx = std::min((max_rows + rows_per_wg - 1) / rows_per_wg, std::max(1, 8192 / c->n_chunks));
+    gx = std::max(1, std::min(gx, c->gap_parts / c->n_chunks));
+    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx); else launch_gap_lpr<1>(c, gx);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = true;
-    if (grid_out) *grid_out = grid;
+    if (grid_out) *grid_out = gx * c->n_chunks;
     return CHICLE_OK;
 }
 
@@ -502,8 +508,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->row_chunk_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
     c->chunk_first_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     c->list_base_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
-    c->part_loss = (double *)carve(c, sizeof(double) * GAP_PARTS);
-    c->part_conj = (double *)carve(c, sizeof(double) * GAP_PARTS);
+    c->gap_parts = std::max(GAP_PARTS, 2 * n_chunks);
+    c->part_loss = (double *)carve(c, sizeof(double) * (size_t)c->gap_parts);
+    c->part_conj = (double *)carve(c, sizeof(double) * (size_t)c->gap_parts);
     c->part_wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
     c->part_unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
     c->gap_out = (double *)carve(c, sizeof(double) * 4);
