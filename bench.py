@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--size", default="full")
     ap.add_argument("--solver", default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (untimed), as a reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the K local solvers run concurrently on a single MI355X and "
@@ -96,6 +98,13 @@ def main():
     total = args.warmup + args.steps
     perms = [g.upload_perm(round_permutations(cfg["seed"], r, rows)) for r in range(total)]
     g.set_profiling(True)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     torch.cuda.synchronize()
 
     def nxt(r):
