@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--size", default="full")
     ap.add_argument("--solver", default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-time-to-gap", action="store_true")
+    ap.add_argument("--gap-round-cap", type=int, default=100)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (untimed), as a reference for HBM byte counters")
     args = ap.parse_args()
@@ -160,6 +162,16 @@ def main():
                      "algorithmic_bytes": abytes},
     }
     g.close()
+    if not args.no_time_to_gap:
+        # from alpha = 0, w = 0 to a duality gap of 1e-3 of its initial value: wall clock over local
+        # epoch + aggregate + gap of every round, visiting orders already in HBM
+        from paper_1909_04885_amd.sweep import run_to_gap
+        res = run_to_gap(p, K, lambda r, rws: round_permutations(cfg["seed"], r, rws), 1e-3,
+                         max_rounds=args.gap_round_cap, table=table)
+        out["time_to_gap"] = {"target": "gap <= 1e-3 x gap(alpha=0, w=0)", "rounds": res["rounds_to_target"],
+                              "ms": None if res["seconds_to_target"] is None else 1e3 * res["seconds_to_target"],
+                              "round_cap": args.gap_round_cap, "final_gap": res["gaps"][-1],
+                              "initial_gap": res["gaps"][0]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(p, cfg, table, K)
     print(json.dumps(out), flush=True)

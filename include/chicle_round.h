@@ -121,12 +121,57 @@ int chicle_load_chunk_dense(chicle_ctx *ctx, int32_t chunk_id, int32_t n_rows, c
 int chicle_balance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const int32_t *speed_q,
                    int32_t *chunk_to_solver_out);
 
+/* Iteration time under the projection model of the evaluation (Sections 5.3 and 5.4), in units of
+ * "one task that holds 1/base_nodes of the data, on a full-speed node" (host, pure).
+ *   K_tasks     > 0: that many equal micro-tasks run in waves over the nodes; 0: uni-tasks, one per
+ *               node, each sized to its node's speed
+ *   nodes       nodes available;  n_slow of them take slow_factor (> 0) times as long per task
+ * Equal nodes: base/K * ceil(K/nodes) for micro-tasks, base/nodes for uni-tasks.  Mixed nodes: the
+ * shortest schedule with i tasks on every slow and j on every fast node, max(i*slow_factor, j)*base/K;
+ * uni-tasks finish together, base / (n_fast + n_slow/slow_factor).  Returns a negative value for
+ * invalid arguments. */
+double chicle_projected_iteration_time(int32_t K_tasks, int32_t nodes, int32_t n_slow, double slow_factor,
+                                       int32_t base_nodes);
+
+/* Elastic scaling policy, growing from K_old to K_new solvers (Section 4.5; Section 5.3 adds that the
+ * chunks moved to new tasks are picked randomly from each old task).  Host, pure, integers only.
+ * Every old solver hands over floor(count * (K_new - K_old) / K_new) of its chunks: those with the
+ * smallest draw[chunk] (ties: smaller chunk id).  Handed-over chunks, old solver by old solver in pick
+ * order, go to solvers K_old, K_old+1, .., K_new-1, K_old, .. in turn.  draw: one caller-supplied random
+ * word per chunk.  in and out may not overlap.  Errors: EINVAL. */
+int chicle_scale_out(const int32_t *chunk_to_solver, int32_t n_chunks, int32_t K_old, int32_t K_new,
+                     const uint32_t *draw, int32_t *chunk_to_solver_out);
+
+/* Elastic scaling policy, shrinking to K_new < K_old solvers (Section 4.5: chunks of the workers to be
+ * freed are redistributed round robin).  Chunks of solvers K_new .. K_old-1, freed solver by freed
+ * solver in ascending chunk id, go to solvers 0, 1, .., K_new-1, 0, .. in turn.  Errors: EINVAL. */
+int chicle_scale_in(const int32_t *chunk_to_solver, int32_t n_chunks, int32_t K_old, int32_t K_new,
+                    int32_t *chunk_to_solver_out);
+
+/* Rebalancing policy (Section 4.5), one call between two iterations.  Host, pure.
+ *   chunk_load   load of every chunk (stored entries)
+ *   unit_time    n_iterations x K row-major: runtime per unit of load that solver k showed in each of
+ *                the last n_iterations iterations (> 0); a solver's rate is the median of its column
+ *   max_moves    chunks moved at most in this call (the policy shifts load over several iterations)
+ *   chunk_to_solver  table, updated in place;  n_moved_out (may be NULL) receives the number moved
+ * Repeatedly the solver with the longest projected time rate*load gives its lightest chunk (ties: the
+ * larger chunk id) to the solver with the shortest one, and stops when their difference is no larger
+ * than the time that chunk would take on the receiver.  Errors: EINVAL. */
+int chicle_rebalance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const double *unit_time,
+                     int32_t n_iterations, int32_t max_moves, int32_t *chunk_to_solver, int32_t *n_moved_out);
+
 /* Scheduler step between iterations: give every chunk to one of K solvers (host table of n_chunks
  * entries in [0, K)); sigma becomes K; every solver's private vector is re-seeded with w.  A solver
  * may own no chunk.  alpha is not touched.  A solver's local rows are its chunks in ascending chunk id,
  * rows ascending inside a chunk.  Legal in LOADING (all chunks loaded, row counts summing to n_total)
  * and READY.  Errors: EINVAL, ESTATE. */
 int chicle_assign(chicle_ctx *ctx, int32_t K, const int32_t *chunk_to_solver);
+
+/* Runtime of every solver's last local pass in milliseconds (host out, K entries), from the device's
+ * constant-rate clock read at the start and at the end of the solver's workgroup: the task runtimes
+ * the rebalancing policy learns from (Section 4.5).  Synchronises the stream.  Errors: ESTATE before
+ * the first local epoch, EDEVICE. */
+int chicle_solver_ms(chicle_ctx *ctx, float *ms_out);
 
 /* Rows owned by each solver under the current assignment (host out, K entries). */
 int chicle_solver_rows(chicle_ctx *ctx, int64_t *rows_out);

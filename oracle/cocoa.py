@@ -97,10 +97,8 @@ def projected_round_time(K_tasks: Optional[int], nodes: int, base_nodes: int = 1
         capacity = n_fast * 1.0 + n_slow / slow_factor
         return base_nodes / capacity
     best = None
-    for i in range(0, K_tasks // max(n_slow, 1) + 1):
-        rest = K_tasks - i * n_slow
-        if rest < 0:
-            break
+    for i in range(0, -(-K_tasks // max(n_slow, 1)) + 1):      # up to all tasks on the slow nodes
+        rest = max(K_tasks - i * n_slow, 0)
         j = -(-rest // n_fast) if n_fast else (0 if rest == 0 else None)
         if j is None:
             continue

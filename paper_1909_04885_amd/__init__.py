@@ -4,4 +4,5 @@
 `include/chicle_round.h`); every step of the round runs in that library's HIP kernels.  PyTorch is
 used only to allocate device memory and to supply the HIP stream.
 """
-from .binding import ChicleError, ChicleRound, balance, library_path, load_library  # noqa: F401
+from .binding import (ChicleError, ChicleRound, balance, library_path, load_library,  # noqa: F401
+                      projected_iteration_time, rebalance, scale_in, scale_out)

@@ -28,6 +28,8 @@ EXPORTS = [
     "chicle_get_w", "chicle_set_w", "chicle_get_delta_w", "chicle_get_alpha", "chicle_set_alpha",
     "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
+    "chicle_solver_ms", "chicle_projected_iteration_time", "chicle_scale_out", "chicle_scale_in",
+    "chicle_rebalance",
 ]
 
 
@@ -82,6 +84,11 @@ def load_library():
         "chicle_last_kernel_ms": (ctypes.c_int, [vp, i32, ctypes.POINTER(ctypes.c_float)]),
         "chicle_last_error": (ctypes.c_char_p, [vp]),
         "chicle_destroy": (None, [vp]),
+        "chicle_solver_ms": (ctypes.c_int, [vp, vp]),
+        "chicle_projected_iteration_time": (dbl, [i32, i32, i32, dbl, i32]),
+        "chicle_scale_out": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
+        "chicle_scale_in": (ctypes.c_int, [vp, i32, i32, i32, vp]),
+        "chicle_rebalance": (ctypes.c_int, [vp, i32, i32, vp, i32, i32, vp, ctypes.POINTER(i32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -111,6 +118,58 @@ def balance(chunk_load: Sequence[int], K: int, speed_q: Optional[Sequence[int]] 
     if rc != OK:
         raise ChicleError(rc, "chicle_balance")
     return out
+
+
+def projected_iteration_time(K_tasks: Optional[int], nodes: int, n_slow: int = 0, slow_factor: float = 1.0,
+                             base_nodes: int = 16) -> float:
+    """chicle_projected_iteration_time; K_tasks None (or 0) selects uni-tasks."""
+    L = load_library()
+    t = L.chicle_projected_iteration_time(int(K_tasks or 0), int(nodes), int(n_slow), float(slow_factor),
+                                          int(base_nodes))
+    if t < 0:
+        raise ChicleError(EINVAL, "chicle_projected_iteration_time")
+    return t
+
+
+def scale_out(table, K_old: int, K_new: int, draw) -> np.ndarray:
+    """chicle_scale_out: new solvers receive randomly picked chunks of every old solver (host only)."""
+    L = load_library()
+    t = _host(table, np.int32)
+    dr = _host(draw, np.uint32)
+    if dr.size != t.size:
+        raise ChicleError(EINVAL, "one draw per chunk")
+    out = np.empty_like(t)
+    rc = L.chicle_scale_out(_ptr(t), t.size, K_old, K_new, _ptr(dr), _ptr(out))
+    if rc != OK:
+        raise ChicleError(rc, "chicle_scale_out")
+    return out
+
+
+def scale_in(table, K_old: int, K_new: int) -> np.ndarray:
+    """chicle_scale_in: chunks of the freed solvers go round robin to the remaining ones (host only)."""
+    L = load_library()
+    t = _host(table, np.int32)
+    out = np.empty_like(t)
+    rc = L.chicle_scale_in(_ptr(t), t.size, K_old, K_new, _ptr(out))
+    if rc != OK:
+        raise ChicleError(rc, "chicle_scale_in")
+    return out
+
+
+def rebalance(chunk_load, K: int, unit_time, table, max_moves: int):
+    """chicle_rebalance: returns (new table, chunks moved).  unit_time: iterations x K (host only)."""
+    L = load_library()
+    load = _host(chunk_load, np.int64)
+    ut = _host(np.atleast_2d(unit_time), np.float64)
+    t = _host(table, np.int32).copy()
+    if ut.shape[1] != K or t.size != load.size:
+        raise ChicleError(EINVAL, "unit_time is iterations x K, one table entry per chunk")
+    moved = ctypes.c_int32(0)
+    rc = L.chicle_rebalance(_ptr(load), load.size, K, _ptr(ut), ut.shape[0], int(max_moves), _ptr(t),
+                            ctypes.byref(moved))
+    if rc != OK:
+        raise ChicleError(rc, "chicle_rebalance")
+    return t, int(moved.value)
 
 
 class ChicleRound:
@@ -189,6 +248,11 @@ class ChicleRound:
     def solver_rows(self) -> np.ndarray:
         out = np.zeros(self.K, dtype=np.int64)
         self._check(self._L.chicle_solver_rows(self._h, _ptr(out)))
+        return out
+
+    def solver_ms(self) -> np.ndarray:
+        out = np.empty(self.K, dtype=np.float32)
+        self._check(self._L.chicle_solver_ms(self._h, _ptr(out)))
         return out
 
     def get_assignment(self):

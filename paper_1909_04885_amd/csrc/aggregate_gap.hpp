@@ -147,6 +147,72 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
     block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);
 }
 
+// The same row pass where the columns are numbered by popularity: the first n_hot entries of w are
+// copied into LDS once per workgroup and the frequent columns of every row are gathered from there;
+// only the rare columns go to the cache hierarchy.  1024 threads; dynamic LDS = n_hot * sizeof(WT).
+constexpr int GAP_HOT_THREADS = 1024;
+constexpr int GAP_HOT_BYTES = 48 * 1024;
+
+template <int LOSS, int LPR, typename WT>
+__global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkDev *__restrict__ chunks,
+                                                                    const WT *__restrict__ w, int n_hot,
+                                                                    double *part_loss, double *part_conj)
+{
+    extern __shared__ __align__(16) unsigned char gap_hot_raw[];
+    WT *hot = reinterpret_cast<WT *>(gap_hot_raw);
+    __shared__ double ra[GAP_HOT_THREADS / 64], rb[GAP_HOT_THREADS / 64];
+    constexpr int GROUPS = GAP_HOT_THREADS / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int grp = threadIdx.x / LPR;
+    const ChunkDev &ch = chunks[blockIdx.y];
+    const int n_rows = ch.n_rows;
+    const int32_t *__restrict__ rp = ch.row_ptr;
+    const int32_t *__restrict__ col = ch.col;
+    const float *__restrict__ val = ch.val;
+    const int stride = gridDim.x * GROUPS;
+    const int first = blockIdx.x * GROUPS + grp;
+    for (int i = threadIdx.x; i < n_hot; i += GAP_HOT_THREADS) hot[i] = w[i];
+    __syncthreads();
+    double s_loss = 0.0, s_conj = 0.0;
+    for (int r0 = first; r0 < n_rows; r0 += 2 * stride) {
+        const int r1 = r0 + stride;
+        const bool two = r1 < n_rows;
+        const int b0 = rp[r0], e0 = rp[r0 + 1];
+        const int b1 = two ? rp[r1] : 0, e1 = two ? rp[r1 + 1] : 0;
+        WT z0 = 0, z1 = 0;
+        int p0 = b0 + sub, p1 = b1 + sub;
+        while (p0 < e0 || p1 < e1) {
+            int c0 = 0, c1 = 0;
+            float v0 = 0.f, v1 = 0.f;
+            if (p0 < e0) { c0 = col[p0]; v0 = val[p0]; }
+            if (p1 < e1) { c1 = col[p1]; v1 = val[p1]; }
+            const WT w0 = c0 < n_hot ? hot[c0] : w[c0];
+            const WT w1 = c1 < n_hot ? hot[c1] : w[c1];
+            z0 += (WT)v0 * w0;
+            z1 += (WT)v1 * w1;
+            p0 += LPR; p1 += LPR;
+        }
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) { z0 += __shfl_xor(z0, o, 64); z1 += __shfl_xor(z1, o, 64); }
+        if (sub == 0) {
+            gap_row_terms<LOSS, WT>(ch.st + r0, z0, s_loss, s_conj);
+            if (two) gap_row_terms<LOSS, WT>(ch.st + r1, z1, s_loss, s_conj);
+        }
+    }
+    s_loss = wave_sum_d(s_loss);
+    s_conj = wave_sum_d(s_conj);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { ra[wave] = s_loss; rb[wave] = s_conj; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0, b = 0.0;
+        for (int i = 0; i < GAP_HOT_THREADS / 64; ++i) { a += ra[i]; b += rb[i]; }
+        const int part = blockIdx.y * gridDim.x + blockIdx.x;
+        part_loss[part] = a;
+        part_conj[part] = b;
+    }
+}
+
 // Dense rows: LPR lanes per row, strided over the d columns.  Same grid as the sparse kernel.
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks, int d,

@@ -17,6 +17,7 @@
 #include "device_types.hpp"
 #include "gram_join.hpp"
 #include "layout.hpp"
+#include "policies.hpp"
 #include "sdca_batched.hpp"
 #include "sdca_rowwise.hpp"
 
@@ -87,6 +88,9 @@ struct chicle_ctx {
     double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
            *gap_out = nullptr;
     int *err_dev = nullptr;
+    long long *ticks_dev = nullptr;   // 2 per solver: clock at start / end of its last pass
+    int wall_khz = 0;                 // rate of that clock
+    bool epoch_ran = false;
 
     // host mirrors
     std::vector<ChunkDev> chunks;
@@ -97,7 +101,7 @@ struct chicle_ctx {
     std::vector<int32_t> chunk_to_solver;
     std::vector<SolverDev> solvers;
     int max_list = 0;
-    int gap_lpr = 64, gap_items = 0;
+    int gap_lpr = 64, gap_items = 0, gap_hot_grid = 0;
     int gap_parts = 0;         // length of the partial-sum arrays of the gap row kernels
 
     bool profiling = false;
@@ -155,6 +159,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += 2 * align_up(sizeof(double) * (size_t)std::max(GAP_PARTS, 2 * n_chunks)) + 2 * align_up(sizeof(double) * WSQ_PARTS);
     s += align_up(sizeof(double) * 4);
     s += align_up(sizeof(int));
+    s += align_up(sizeof(long long) * 2 * (size_t)max_solvers);
     return s;
 }
 
@@ -222,6 +227,7 @@ RoundScalars scalars(const chicle_ctx *c)
     s.inv_c = (float)(1.0 / cc);
     s.inv_sigma = (float)(1.0 / (double)c->K);
     s.K = c->K;
+    s.ticks = c->ticks_dev;
     return s;
 }
 
@@ -347,7 +353,12 @@ template <int LOSS, int LPRG, typename WT>
 void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w)
 {
     const dim3 grid(grid_x, c->n_chunks);
-    if (c->dense)
+    if (c->gap_hot_grid > 0) {
+        const int n_hot = (int)std::min<int64_t>(c->d, GAP_HOT_BYTES / (int)sizeof(WT));
+        hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, LPRG, WT>), dim3(c->gap_hot_grid, c->n_chunks),
+                           dim3(GAP_HOT_THREADS), n_hot * sizeof(WT), c->stream, c->chunks_dev, w, n_hot,
+                           c->part_loss, c->part_conj);
+    } else if (c->dense)
         hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev,
                            (int)c->d, w, c->part_loss, c->part_conj);
     else
@@ -385,6 +396,14 @@ int run_row_pass(chicle_ctx *c, int *grid_out)
     const int rows_per_wg = 2 * (256 / c->gap_lpr);
     int gx = std::min((max_rows + rows_per_wg - 1) / rows_per_wg, std::max(1, 8192 / c->n_chunks));
     gx = std::max(1, std::min(gx, c->gap_parts / c->n_chunks));
+    // popularity-numbered columns: frequent part of w from LDS, few large workgroups per chunk
+    c->gap_hot_grid = 0;
+    if (c->renumbered && !c->dense && c->gap_lpr <= 16) {
+        const int rows_per_hot_wg = 2 * (GAP_HOT_THREADS / c->gap_lpr);
+        gx = std::max(1, std::min(std::min(2, (max_rows + rows_per_hot_wg - 1) / rows_per_hot_wg),
+                                  c->gap_parts / c->n_chunks));
+        c->gap_hot_grid = gx;
+    }
     if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx); else launch_gap_lpr<1>(c, gx);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = true;
@@ -396,8 +415,7 @@ int choose_lpr(double avg_row_len)
 {
     if (avg_row_len <= 6) return 4;
     if (avg_row_len <= 12) return 8;
-    if (avg_row_len <= 24) return 16;
-    if (avg_row_len <= 48) return 32;
+    if (avg_row_len <= 48) return 16;
     return 64;
 }
 
@@ -515,7 +533,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->part_unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
     c->gap_out = (double *)carve(c, sizeof(double) * 4);
     c->err_dev = (int *)carve(c, sizeof(int));
-    if (!c->err_dev) { delete c; return CHICLE_ENOMEM; }
+    c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
+    if (!c->err_dev || !c->ticks_dev) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -524,7 +543,13 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
               hipMemsetAsync(c->tmp_a, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->tmp_b, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
-              hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess;
+              hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess &&
+              hipMemsetAsync(c->ticks_dev, 0, sizeof(long long) * 2 * (size_t)max_solvers, c->stream) == hipSuccess;
+    {
+        int dev = 0;
+        ok = ok && hipGetDevice(&dev) == hipSuccess &&
+             hipDeviceGetAttribute(&c->wall_khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && c->wall_khz > 0;
+    }
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
@@ -823,6 +848,7 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     seg_end(c, CHICLE_SEG_LOCAL_EPOCH);
     if (rc) return rc;
     c->state = ST_EPOCH_DONE;
+    c->epoch_ran = true;
     return CHICLE_OK;
 }
 
@@ -955,6 +981,68 @@ int chicle_get_assignment(chicle_ctx *c, int32_t *chunk_to_solver_out, int32_t *
     if (c->state == ST_LOADING) return fail(c, CHICLE_ESTATE, "no assignment yet");
     if (chunk_to_solver_out) std::memcpy(chunk_to_solver_out, c->chunk_to_solver.data(), sizeof(int32_t) * (size_t)c->n_chunks);
     if (K_out) *K_out = c->K;
+    return CHICLE_OK;
+}
+
+int chicle_solver_ms(chicle_ctx *c, float *ms_out)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (!ms_out) return fail(c, CHICLE_EINVAL, "output is NULL");
+    if (!c->epoch_ran) return fail(c, CHICLE_ESTATE, "no local epoch has run");
+    std::vector<long long> t(2 * (size_t)c->K);
+    HIP_TRY(c, hipMemcpyAsync(t.data(), c->ticks_dev, sizeof(long long) * t.size(), hipMemcpyDeviceToHost, c->stream));
+    const int rc = check_deferred(c);
+    if (rc) return rc;
+    for (int k = 0; k < c->K; ++k) ms_out[k] = (float)((double)(t[2 * k + 1] - t[2 * k]) / (double)c->wall_khz);
+    return CHICLE_OK;
+}
+
+double chicle_projected_iteration_time(int32_t K_tasks, int32_t nodes, int32_t n_slow, double slow_factor,
+                                       int32_t base_nodes)
+{
+    if (K_tasks < 0 || nodes <= 0 || n_slow < 0 || n_slow > nodes || base_nodes <= 0 ||
+        (n_slow > 0 && !(slow_factor > 0.0)))
+        return -1.0;
+    return projected_iteration_time(K_tasks, nodes, n_slow, slow_factor, base_nodes);
+}
+
+static bool table_ok(const int32_t *t, int32_t n_chunks, int32_t K)
+{
+    if (!t || n_chunks < 0 || K <= 0) return false;
+    for (int32_t i = 0; i < n_chunks; ++i)
+        if (t[i] < 0 || t[i] >= K) return false;
+    return true;
+}
+
+int chicle_scale_out(const int32_t *chunk_to_solver, int32_t n_chunks, int32_t K_old, int32_t K_new,
+                     const uint32_t *draw, int32_t *chunk_to_solver_out)
+{
+    if (!table_ok(chunk_to_solver, n_chunks, K_old) || K_new <= K_old || !draw || !chunk_to_solver_out)
+        return CHICLE_EINVAL;
+    scale_out_table(n_chunks, chunk_to_solver, K_old, K_new, draw, chunk_to_solver_out);
+    return CHICLE_OK;
+}
+
+int chicle_scale_in(const int32_t *chunk_to_solver, int32_t n_chunks, int32_t K_old, int32_t K_new,
+                    int32_t *chunk_to_solver_out)
+{
+    if (!table_ok(chunk_to_solver, n_chunks, K_old) || K_new <= 0 || K_new >= K_old || !chunk_to_solver_out)
+        return CHICLE_EINVAL;
+    scale_in_table(n_chunks, chunk_to_solver, K_old, K_new, chunk_to_solver_out);
+    return CHICLE_OK;
+}
+
+int chicle_rebalance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const double *unit_time,
+                     int32_t n_iterations, int32_t max_moves, int32_t *chunk_to_solver, int32_t *n_moved_out)
+{
+    if (!chunk_load || !table_ok(chunk_to_solver, n_chunks, K) || !unit_time || n_iterations <= 0 || max_moves < 0)
+        return CHICLE_EINVAL;
+    for (int32_t i = 0; i < n_chunks; ++i)
+        if (chunk_load[i] < 0) return CHICLE_EINVAL;
+    for (int64_t i = 0; i < (int64_t)n_iterations * K; ++i)
+        if (!(unit_time[i] > 0.0) || !std::isfinite(unit_time[i])) return CHICLE_EINVAL;
+    const int moved = rebalance_table(chunk_load, n_chunks, K, unit_time, n_iterations, max_moves, chunk_to_solver);
+    if (n_moved_out) *n_moved_out = moved;
     return CHICLE_OK;
 }
 

@@ -41,7 +41,15 @@ struct RoundScalars {
     float inv_c;    // sigma / (lambda n)
     float inv_sigma;
     int32_t K;
+    long long *ticks;   // per solver: constant-rate clock at the start and at the end of its pass
 };
+
+// Start / end stamps of a solver's pass (Section 4.5: task runtimes are what the rebalancing policy
+// learns from).  One lane per workgroup writes them.
+__device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int which)
+{
+    if (threadIdx.x == 0 && sc.ticks) sc.ticks[2 * blockIdx.x + which] = (long long)wall_clock64();
+}
 
 constexpr int ERR_PERM_RANGE = 1;
 

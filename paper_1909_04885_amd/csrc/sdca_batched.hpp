@@ -128,6 +128,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     int *l_prefix = reinterpret_cast<int *>(l_desc + max_list);
     const SolverDev S = solvers[blockIdx.x];
     const int tid = threadIdx.x;
+    stamp_solver(sc, 0);
     for (int i = tid; i < S.n_chunks; i += BATCHED_THREADS) {
         l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
         l_prefix[i] = solver_prefix[S.list_begin + i];
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const bool is_chain = tid < 64;
     const bool is_service = tid >= 64 + BATCH * LPR;
     const int lane = tid & 63;
-    const int hl = tid - 64, rho = hl >> 3, sub = hl & (LPR - 1);     // helper coordinates
+    const int hl = tid - 64, rho = hl / LPR, sub = hl & (LPR - 1);     // helper coordinates
     const int sw = (tid - 64 - BATCH * LPR) >> 6;                     // service wavefront 0 or 1
 
     // service pipeline registers (wavefront 9: one lane per row of a block)
@@ -165,7 +166,10 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     int in_len = 0;
     float x_carry = 0.f;
     int hb_target = 0;
-    if (nb == 0) return;                             // a solver without rows (uniform for the workgroup)
+    if (nb == 0) {                                   // a solver without rows (uniform for the workgroup)
+        stamp_solver(sc, 1);
+        return;
+    }
 
     for (int i = -5; i <= nb; ++i) {
         if (is_chain) {
@@ -282,9 +286,8 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) part += g_v[e] * (cold_v[e] + hot_v[e]);
-                part += __shfl_xor(part, 1, 64);
-                part += __shfl_xor(part, 2, 64);
-                part += __shfl_xor(part, 4, 64);
+#pragma unroll
+                for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o, 64);
                 if (sub == 0) {
                     const int ring = (i + 1) & (RING - 1);
                     float t0 = 0.f, lo = 0.f, hi = 0.f;
@@ -312,6 +315,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         __syncthreads();
     }
     for (int i = tid; i < n_hot; i += BATCHED_THREADS) u[i] = hot[i];
+    stamp_solver(sc, 1);
 }
 
 }  // namespace chicle

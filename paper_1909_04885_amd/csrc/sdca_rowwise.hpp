@@ -97,6 +97,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
     ChunkDev *l_desc = reinterpret_cast<ChunkDev *>(rw_smem);
     int *l_prefix = reinterpret_cast<int *>(l_desc + max_list);
     const int tid = threadIdx.x;
+    stamp_solver(sc, 0);
     for (int i = tid; i < S.n_chunks; i += BLOCK) {
         l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
         l_prefix[i] = solver_prefix[S.list_begin + i];
@@ -182,6 +183,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         for (int e = 0; e < EPT; ++e) { c_c[e] = n_c[e]; c_v[e] = n_v[e]; }
         __syncthreads();   // ring slots written this step are read next step; orders scatter before gather
     }
+    stamp_solver(sc, 1);
 }
 
 // Dense rows.  The private vector is staged in LDS when it fits (V_LDS), else it stays in HBM.
@@ -201,6 +203,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
     float *v_lds = reinterpret_cast<float *>(lists + 2 * max_list);
     float *v_glb = u_all + (int64_t)blockIdx.x * ld_v;
     const int tid = threadIdx.x;
+    stamp_solver(sc, 0);
     for (int i = tid; i < S.n_chunks; i += BLOCK) {
         l_chunk[i] = solver_chunks[S.list_begin + i];
         l_prefix[i] = solver_prefix[S.list_begin + i];
@@ -239,6 +242,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
     }
     if (V_LDS)
         for (int i = tid; i < d; i += BLOCK) v_glb[i] = v_lds[i];
+    stamp_solver(sc, 1);
 }
 
 }  // namespace chicle

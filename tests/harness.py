@@ -26,11 +26,29 @@ def rel_l2(got: np.ndarray, ref: np.ndarray, floor: float) -> float:
     return float(np.linalg.norm(got.astype(np.float64) - ref)) / den
 
 
+def greedy_tables(cfg, p, oracle_mod, binding_mod):
+    """The configured schedule: a greedy balanced table from each side whenever K changes."""
+    loads = p.chunk_nnz()
+
+    def tables(r, K_prev, t_prev):
+        Kr = k_for_round(cfg, r)
+        if Kr == K_prev:
+            return None
+        sp = speeds_for(cfg, Kr)
+        return Kr, oracle_mod.assign_greedy(loads, Kr, sp), binding_mod.balance(loads, Kr, sp)
+    return tables
+
+
 def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sample_solvers=None,
-                 check_alpha_every=0, log=None, ahead=False):
-    """Returns a dict of per-round records; raises AssertionError on the first violation."""
+                 check_alpha_every=0, log=None, ahead=False, tables=None, max_solvers=None):
+    """Returns a dict of per-round records; raises AssertionError on the first violation.
+
+    `tables(r, K_prev, table_prev)` returns None (no change before round r) or (K, table from the
+    oracle side, table from the library side); default: the configured greedy schedule."""
     o = oracle_mod.OracleCoCoA.from_problem(p)
-    maxK = max(k for _, k in cfg["schedule"])
+    maxK = max_solvers or max(k for _, k in cfg["schedule"])
+    tables = tables or greedy_tables(cfg, p, oracle_mod, binding_mod)
+    table = None
     g = binding_mod.ChicleRound.from_problem(p, max_solvers=maxK)
     g.set_solver(solver)
     rounds = cfg["rounds"] if rounds is None else rounds
@@ -39,13 +57,12 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
     loads = p.chunk_nnz()
     next_dev = None      # visiting orders of round r already in HBM (announced during round r - 1)
     for r in range(rounds):
-        Kr = k_for_round(cfg, r)
-        if Kr != K:
-            K = Kr
-            sp = speeds_for(cfg, K)
-            t_ref = oracle_mod.assign_greedy(loads, K, sp)
-            t_gpu = binding_mod.balance(loads, K, sp)
+        change = tables(r, K, table)
+        if change is not None:
+            K, t_ref, t_gpu = change
+            t_ref = np.asarray(t_ref, dtype=np.int32)
             assert np.array_equal(t_ref, t_gpu), "chunk -> solver table differs at round %d" % r
+            table = t_ref
             alpha_before = [g.get_alpha(c) for c in range(min(p.n_chunks, 4))] if r > 0 else None
             o.assign(K, t_ref)
             g.assign(K, t_gpu)
@@ -62,7 +79,7 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
             # announce the next round's orders unless the schedule reassigns chunks before it
             cur_dev = next_dev if next_dev is not None else g.upload_perm(perms)
             next_dev = None
-            if r + 1 < rounds and k_for_round(cfg, r + 1) == K:
+            if r + 1 < rounds and tables(r + 1, K, table) is None:
                 next_dev = g.upload_perm(round_permutations(cfg["seed"], r + 1, o.rows_per_solver()))
             g.local_epoch_ahead(cur_dev, next_dev)
         wnorm = float(np.linalg.norm(o.w))

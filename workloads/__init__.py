@@ -7,4 +7,4 @@ neither the oracle nor the GPU library.
 """
 from .configs import CONFIGS, get_config          # noqa: F401
 from .generate import Problem, make_problem        # noqa: F401
-from .permutations import solver_permutation, round_permutations  # noqa: F401
+from .permutations import chunk_draws, solver_permutation, round_permutations  # noqa: F401

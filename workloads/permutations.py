@@ -25,3 +25,11 @@ def solver_permutation(seed: int, rnd: int, solver: int, n_local: int) -> np.nda
 def round_permutations(seed: int, rnd: int, rows_per_solver) -> list:
     """One permutation per solver for round `rnd`; `rows_per_solver[k]` = rows solver k owns."""
     return [solver_permutation(seed, rnd, k, int(nk)) for k, nk in enumerate(rows_per_solver)]
+
+
+def chunk_draws(seed: int, rnd: int, n_chunks: int) -> np.ndarray:
+    """One random 32-bit word per chunk for a scaling step before round `rnd` (input to the
+    random chunk picks of the scale-out policy), uint32."""
+    key = np.array([np.uint64(seed) ^ np.uint64(0x5CA1E), np.uint64(rnd)], dtype=np.uint64)
+    g = np.random.Generator(np.random.Philox(key=key))
+    return g.integers(0, 2 ** 32, n_chunks, dtype=np.uint64).astype(np.uint32)
