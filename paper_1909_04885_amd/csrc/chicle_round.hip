@@ -315,14 +315,15 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
     c->ahead_perm = nullptr;
     if (perm_next) HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));   // everything enqueued so far
     const int ml = std::max(c->max_list, 1);
-    const int n_hot = (int)std::min<int64_t>(HOT_COLS, c->d);
-    const size_t sh = sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + sizeof(float) * (size_t)n_hot;
+    const size_t hot_off = (sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + 15) & ~(size_t)15;
+    const int n_hot = (int)std::min<int64_t>((int64_t)((LDS_BYTES - hot_off) / sizeof(double)) & ~(int64_t)63, c->d);
+    const size_t sh = hot_off + sizeof(double) * (size_t)n_hot;
     auto kern = sdca_batched_csr<LOSS>;
     HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
     seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
     hipLaunchKernelGGL(kern, dim3(c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
                        c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u, c->ld_v, ml,
-                       n_hot, sc, c->err_dev);
+                       n_hot, (int)hot_off, sc, c->err_dev);
     seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
     HIP_TRY(c, hipGetLastError());
     if (perm_next) {

@@ -33,7 +33,10 @@ constexpr int HELPER_WAVES = BATCH * LPR / 64;
 constexpr int SERVICE_WAVES = 2;              // row resolution and tile staging
 constexpr int BATCHED_THREADS = 64 + BATCH * LPR + 64 * SERVICE_WAVES;
 constexpr int RING = 8;
-constexpr int HOT_COLS = 12288;               // head of the private vector kept in LDS (popular columns)
+// The head of the private vector (popular columns) is kept in LDS for the whole pass, in double: LDS
+// atomic adds on doubles run at the rate of the LDS pipeline on this hardware, those on floats are
+// serialised lane by lane (about 3 cycles per lane).  It takes whatever LDS the rest leaves free.
+constexpr int LDS_BYTES = 160 * 1024;
 
 // What the helpers know about one row of a block.
 struct RowSlot {
@@ -114,13 +117,13 @@ __device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, 
 
 // One workgroup per solver: wavefront 0 runs the chain, eight wavefronts gather and scatter, two
 // resolve the rows of coming blocks and stage the tiles.
-// Dynamic LDS: BatchedShared, then max_list chunk descriptors, max_list local-row prefixes, n_hot floats.
+// Dynamic LDS: BatchedShared, then max_list chunk descriptors, max_list local-row prefixes, then (at byte offset hot_off) n_hot doubles.
 template <int LOSS>
 __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
     const int32_t *__restrict__ perm, const float *__restrict__ tiles, float *u_all, int64_t ld_v,
-    int max_list, int n_hot, RoundScalars sc, int *err)
+    int max_list, int n_hot, int hot_off, RoundScalars sc, int *err)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     BatchedShared &sh = *reinterpret_cast<BatchedShared *>(smem);
@@ -134,8 +137,8 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
     // columns [0, n_hot) of the private vector live here for the whole pass (it starts at zero)
-    float *hot = reinterpret_cast<float *>(l_prefix + max_list);
-    for (int i = tid; i < n_hot; i += BATCHED_THREADS) hot[i] = 0.f;
+    double *hot = reinterpret_cast<double *>(smem + hot_off);
+    for (int i = tid; i < n_hot; i += BATCHED_THREADS) hot[i] = 0.0;
     if (tid == 0) sh.hb = 0;
     __syncthreads();
     float *u = u_all + (int64_t)blockIdx.x * ld_v;
@@ -166,6 +169,8 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     int in_len = 0;
     float x_carry = 0.f;
     int hb_target = 0;
+    float4 stage[16];                                // service wavefronts: tile part fetched ahead
+    bool staged = false;
     if (nb == 0) {                                   // a solver without rows (uniform for the workgroup)
         stamp_solver(sc, 1);
         return;
@@ -175,16 +180,13 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         if (is_chain) {
             if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry);
         } else if (is_service) {
-            // tiles for iteration i + 1: wavefront 9 stages the own part of T(i+1), wavefront 10 the
-            // cross part of T(i+2); 16 KB each, all loads in flight before the first LDS write
-            const int tb = sw == 0 ? i + 1 : i + 2;
-            const bool have = tb >= 0 && tb < nb;
-            float4 stage[16];
-            if (have) {
-                const float4 *src = reinterpret_cast<const float4 *>(
-                    my_tiles + (int64_t)tb * TILE_FLOATS + (sw == 0 ? BATCH * BATCH : 0));
+            // tiles for iteration i + 1 (wavefront 9: own part of T(i+1), wavefront 10: cross part of
+            // T(i+2), 16 KB each) were fetched into registers during the last iteration
+            {
+                const int buf = (i + 1) & 1;
+                float4 *dst = reinterpret_cast<float4 *>(sw == 0 ? &sh.Tw[buf][0][0] : &sh.Tx[buf][0][0]);
 #pragma unroll
-                for (int j = 0; j < 16; ++j) stage[j] = src[lane + 64 * j];
+                for (int j = 0; j < 16; ++j) dst[lane + 64 * j] = staged ? stage[j] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
             if (sw == 0) {
                 // 1. publish the row of block i + 3 whose state loads were issued last iteration
@@ -221,11 +223,20 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 }
                 p_cur = p_next;
             }
+            // the next iteration's tiles are requested once the helpers have issued their scatters: bulk
+            // loads then queue behind the gather's loads in the vector memory pipeline, not in front of them
+            hb_target += HELPER_WAVES;
+            while (__hip_atomic_load(&sh.hb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < hb_target)
+                __builtin_amdgcn_s_sleep(2);
             {
-                const int buf = (i + 1) & 1;
-                float4 *dst = reinterpret_cast<float4 *>(sw == 0 ? &sh.Tw[buf][0][0] : &sh.Tx[buf][0][0]);
+                const int tb = sw == 0 ? i + 2 : i + 3;
+                staged = tb >= 0 && tb < nb;
+                if (staged) {
+                    const float4 *src = reinterpret_cast<const float4 *>(
+                        my_tiles + (int64_t)tb * TILE_FLOATS + (sw == 0 ? BATCH * BATCH : 0));
 #pragma unroll
-                for (int j = 0; j < 16; ++j) dst[lane + 64 * j] = have ? stage[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int j = 0; j < 16; ++j) stage[j] = src[lane + 64 * j];
+                }
             }
         } else {
             // 4. fetch this lane's segment of the row of block i + 2 (unconditional vector loads; the
@@ -252,7 +263,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
 #pragma unroll
                     for (int e = 0; e < ENT; ++e)
                         if (s_v[e] != 0.f) {
-                            if (s_c[e] < n_hot) atomicAdd(&hot[s_c[e]], coef * s_v[e]);
+                            if (s_c[e] < n_hot) atomicAdd(&hot[s_c[e]], (double)(coef * s_v[e]));
                             else unsafeAtomicAdd(&u[s_c[e]], coef * s_v[e]);
                         }
                     if (sub == 0) {
@@ -281,7 +292,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) {
                     hot_v[e] = 0.f;
-                    if (g_v[e] != 0.f && g_c[e] < n_hot) hot_v[e] = hot[g_c[e]];
+                    if (g_v[e] != 0.f && g_c[e] < n_hot) hot_v[e] = (float)hot[g_c[e]];
                 }
                 float part = 0.f;
 #pragma unroll
@@ -314,7 +325,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         }
         __syncthreads();
     }
-    for (int i = tid; i < n_hot; i += BATCHED_THREADS) u[i] = hot[i];
+    for (int i = tid; i < n_hot; i += BATCHED_THREADS) u[i] = (float)hot[i];
     stamp_solver(sc, 1);
 }
 
