@@ -153,7 +153,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const int sw = (tid - 64 - BATCH * LPR) >> 6;                     // service wavefront 0 or 1
 
     // service pipeline registers (wavefront 9: one lane per row of a block)
-    int p_cur = -1, p_next = -1;                     // visiting-order entries
+    int p_cur = -1;                                  // visiting-order entry read last iteration
     int m_ci = -1, m_r = 0;                          // row being resolved: loads in flight
     int2_a4 m_rp = {0, 0};
     float4_v m_st = {0.f, 0.f, 0.f, 0.f};          // kept whole until it is used (y, alpha, q, rw)
@@ -204,8 +204,8 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 }
                 // 2. issue the state loads of block i + 4 from the order entry read last iteration
                 m_ci = -1;
-                if (i + 4 >= 0 && i + 4 < nb && p_cur >= 0) {
-                    if (p_cur >= S.n_rows) {
+                if (i + 4 >= 0 && i + 4 < nb && (i + 4) * BATCH + lane < S.n_rows) {
+                    if (p_cur < 0 || p_cur >= S.n_rows) {
                         atomicOr(err, ERR_PERM_RANGE);
                     } else {
                         m_ci = find_chunk(l_prefix, S.n_chunks, p_cur);
@@ -215,13 +215,9 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                         m_st = gld_state(ch.st + m_r);
                     }
                 }
-                // 3. read the order entry of block i + 5
-                p_next = -1;
-                if (i + 5 >= 0 && i + 5 < nb) {
-                    const int t = (i + 5) * BATCH + lane;
-                    if (t < S.n_rows) p_next = pk[t];
-                }
-                p_cur = p_next;
+                // 3. read the order entry of block i + 5 (always some valid position: the value is only
+                //    looked at next iteration, under the range test of step 2, so nothing waits for it here)
+                p_cur = gld(pk + min(max((i + 5) * BATCH + lane, 0), S.n_rows - 1));
             }
             // the next iteration's tiles are requested once the helpers have issued their scatters: bulk
             // loads then queue behind the gather's loads in the vector memory pipeline, not in front of them
