@@ -88,6 +88,7 @@ struct chicle_ctx {
     double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
            *gap_out = nullptr;
     int *err_dev = nullptr;
+    int *progress_dev = nullptr;      // per solver: block its batched pass has reached
     long long *ticks_dev = nullptr;   // 2 per solver: clock at start / end of its last pass
     int wall_khz = 0;                 // rate of that clock
     bool epoch_ran = false;
@@ -160,6 +161,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(double) * 4);
     s += align_up(sizeof(int));
     s += align_up(sizeof(long long) * 2 * (size_t)max_solvers);
+    s += align_up(sizeof(int) * (size_t)max_solvers);
     return s;
 }
 
@@ -320,10 +322,12 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
     const size_t sh = hot_off + sizeof(double) * (size_t)n_hot;
     auto kern = sdca_batched_csr<LOSS>;
     HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+    const int first_warmer = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
+    HIP_TRY(c, hipMemsetAsync(c->progress_dev, 0, sizeof(int) * (size_t)c->K, c->stream));
     seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
-    hipLaunchKernelGGL(kern, dim3(c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
-                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u, c->ld_v, ml,
-                       n_hot, (int)hot_off, sc, c->err_dev);
+    hipLaunchKernelGGL(kern, dim3(first_warmer + c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev,
+                       c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u,
+                       c->ld_v, ml, n_hot, (int)hot_off, sc, c->err_dev, c->progress_dev, first_warmer);
     seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
     HIP_TRY(c, hipGetLastError());
     if (perm_next) {
@@ -535,7 +539,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->gap_out = (double *)carve(c, sizeof(double) * 4);
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
-    if (!c->err_dev || !c->ticks_dev) { delete c; return CHICLE_ENOMEM; }
+    c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);

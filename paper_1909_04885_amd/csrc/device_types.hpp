@@ -46,10 +46,11 @@ struct RoundScalars {
 
 // Start / end stamps of a solver's pass (Section 4.5: task runtimes are what the rebalancing policy
 // learns from).  One lane per workgroup writes them.
-__device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int which)
+__device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int solver, int which)
 {
-    if (threadIdx.x == 0 && sc.ticks) sc.ticks[2 * blockIdx.x + which] = (long long)wall_clock64();
+    if (threadIdx.x == 0 && sc.ticks) sc.ticks[2 * solver + which] = (long long)wall_clock64();
 }
+__device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int which) { stamp_solver(sc, blockIdx.x, which); }
 
 constexpr int ERR_PERM_RANGE = 1;
 

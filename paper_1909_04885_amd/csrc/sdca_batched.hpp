@@ -37,6 +37,9 @@ constexpr int RING = 8;
 // atomic adds on doubles run at the rate of the LDS pipeline on this hardware, those on floats are
 // serialised lane by lane (about 3 cycles per lane).  It takes whatever LDS the rest leaves free.
 constexpr int LDS_BYTES = 160 * 1024;
+constexpr int WARM_AHEAD = 6;                 // blocks a warming workgroup may run ahead of its solver
+constexpr int WARM_WAVES = 4;                 // its wavefronts at work
+constexpr int L2_PARTITIONS = 8;              // workgroup i is dispatched to partition i mod 8
 
 // What the helpers know about one row of a block.
 struct RowSlot {
@@ -123,25 +126,71 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
     const int32_t *__restrict__ perm, const float *__restrict__ tiles, float *u_all, int64_t ld_v,
-    int max_list, int n_hot, int hot_off, RoundScalars sc, int *err)
+    int max_list, int n_hot, int hot_off, RoundScalars sc, int *err, int *progress, int first_warmer)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     BatchedShared &sh = *reinterpret_cast<BatchedShared *>(smem);
     ChunkDev *l_desc = reinterpret_cast<ChunkDev *>(smem + sizeof(BatchedShared));
     int *l_prefix = reinterpret_cast<int *>(l_desc + max_list);
-    const SolverDev S = solvers[blockIdx.x];
+    // Workgroups [0, K) are the solvers; workgroup first_warmer + k runs ahead of solver k and only reads
+    // what that solver is about to read, so that the data is in the L2 both share (first_warmer is a
+    // multiple of the number of L2 partitions workgroups are dealt over).
+    const bool warmer = (int)blockIdx.x >= first_warmer;
+    const int sid = warmer ? (int)blockIdx.x - first_warmer : (int)blockIdx.x;
+    if (sid >= sc.K) return;
+    const SolverDev S = solvers[sid];
     const int tid = threadIdx.x;
-    stamp_solver(sc, 0);
+    if (!warmer) stamp_solver(sc, sid, 0);
     for (int i = tid; i < S.n_chunks; i += BATCHED_THREADS) {
         l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
         l_prefix[i] = solver_prefix[S.list_begin + i];
+    }
+    if (warmer) {
+        // WARM_WAVES wavefronts, one block each in turn, one lane per row: order entry -> row extent ->
+        // column ids -> the private vector's lines outside the LDS-resident head.  Nothing is kept.
+        __syncthreads();
+        const int wv = tid >> 6, ln = tid & 63;
+        if (wv >= WARM_WAVES) return;
+        const int n_blocks = (S.n_rows + BATCH - 1) / BATCH;
+        const float *uw = u_all + (int64_t)sid * ld_v;
+        const int32_t *pkw = perm + S.perm_off;
+        for (int b = wv; b < n_blocks; b += WARM_WAVES) {
+            // stay within WARM_AHEAD blocks of the solver (its last value ends every wait)
+            while (__hip_atomic_load(progress + sid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + WARM_AHEAD < b)
+                __builtin_amdgcn_s_sleep(16);
+            const int t = b * BATCH + ln;
+            if (t >= S.n_rows) continue;
+            const int p = pkw[t];
+            if (p < 0 || p >= S.n_rows) continue;
+            const int ci = find_chunk(l_prefix, S.n_chunks, p);
+            const int r = p - l_prefix[ci];
+            const ChunkDev &ch = l_desc[ci];
+            const int2_a4 rp = gld2(ch.row_ptr + r);
+            const int len = min(rp.y - rp.x, GRAM_MAX_ROW);
+            if (len <= 0) continue;
+            float sink = 0.f;
+            for (int e = 0; e < len; e += 16) sink += gld(ch.val + rp.x + e);      // one touch per 64 bytes
+            int cc[GRAM_MAX_ROW];
+#pragma unroll
+            for (int e = 0; e < GRAM_MAX_ROW; ++e) cc[e] = gld(ch.col + rp.x + min(e, len - 1));   // all in flight
+            float uv[GRAM_MAX_ROW];
+#pragma unroll
+            for (int e = 0; e < GRAM_MAX_ROW; ++e) {
+                uv[e] = 0.f;
+                if (cc[e] >= n_hot) uv[e] = uw[cc[e]];
+            }
+#pragma unroll
+            for (int e = 0; e < GRAM_MAX_ROW; ++e) sink += uv[e];
+            asm volatile("" ::"v"(sink));
+        }
+        return;
     }
     // columns [0, n_hot) of the private vector live here for the whole pass (it starts at zero)
     double *hot = reinterpret_cast<double *>(smem + hot_off);
     for (int i = tid; i < n_hot; i += BATCHED_THREADS) hot[i] = 0.0;
     if (tid == 0) sh.hb = 0;
     __syncthreads();
-    float *u = u_all + (int64_t)blockIdx.x * ld_v;
+    float *u = u_all + (int64_t)sid * ld_v;
     const int32_t *pk = perm + S.perm_off;
     const float *my_tiles = tiles + (int64_t)S.tile_begin * TILE_FLOATS;
     const int nb = (S.n_rows + BATCH - 1) / BATCH;
@@ -172,11 +221,13 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     float4 stage[16];                                // service wavefronts: tile part fetched ahead
     bool staged = false;
     if (nb == 0) {                                   // a solver without rows (uniform for the workgroup)
-        stamp_solver(sc, 1);
+        stamp_solver(sc, sid, 1);
         return;
     }
 
     for (int i = -5; i <= nb; ++i) {
+        if (tid == BATCHED_THREADS - 1 && i > 0)
+            __hip_atomic_store(progress + sid, i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (is_chain) {
             if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry);
         } else if (is_service) {
@@ -322,7 +373,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         __syncthreads();
     }
     for (int i = tid; i < n_hot; i += BATCHED_THREADS) u[i] = (float)hot[i];
-    stamp_solver(sc, 1);
+    stamp_solver(sc, sid, 1);
 }
 
 }  // namespace chicle
