@@ -83,6 +83,7 @@ def main():
 
     import torch
     import paper_1909_04885_amd as chicle
+from paper_1909_04885_amd.record_traffic import stored_traffic
     from workloads import get_config, make_problem, round_permutations
 
     cfg = get_config(args.workload, args.size)
@@ -158,7 +159,10 @@ def main():
                 "frac_hbm_peak": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "first": gaps[0], "last": gaps[-1]},
         "roofline": {"kernel": "local_epoch", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     # measured HBM bytes per launch of the chain kernel; null unless they were taken on
+                     # exactly these kernel sources (paper_1909_04885_amd/record_traffic.py)
+                     "traffic": stored_traffic("%s/%s" % (args.workload, args.size)) if args.solver == "auto" else None,
                      "algorithmic_bytes": abytes},
     }
     g.close()
