@@ -83,7 +83,7 @@ def main():
 
     import torch
     import paper_1909_04885_amd as chicle
-from paper_1909_04885_amd.record_traffic import stored_traffic
+    from paper_1909_04885_amd.record_traffic import stored_traffic
     from workloads import get_config, make_problem, round_permutations
 
     cfg = get_config(args.workload, args.size)
