@@ -104,3 +104,25 @@ def test_product_path_has_no_cpu_fallback():
         import paper_1909_04885_amd as m
         with pytest.raises(m.ChicleError):
             m.ChicleRound("hinge", 10, 4, 0.1, 1, 1, True, 40)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_stored_traffic_is_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    from paper_1909_04885_amd import record_traffic as rt
+    rec = {"workload": "w/full", "hbm_bytes_per_launch": 5.0, "source_sha256": rt.source_hash()}
+    f = tmp_path / "t.json"
+    monkeypatch.setattr(rt, "TRAFFIC_FILE", str(f))
+    assert rt.stored_traffic("w/full") is None                 # no record
+    f.write_text(__import__("json").dumps(rec))
+    assert rt.stored_traffic("w/full") == 5.0
+    assert rt.stored_traffic("other/full") is None
+    rec["source_sha256"] = "0" * 64                             # measured on other sources
+    f.write_text(__import__("json").dumps(rec))
+    assert rt.stored_traffic("w/full") is None
