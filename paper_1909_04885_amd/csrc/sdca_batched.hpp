@@ -50,29 +50,6 @@ struct RowSlot {
     float y, alpha, q, rw;
 };
 
-// Resolve local row lr of a solver (lists in global memory) into a RowSlot; len = 0 if unusable.
-__device__ __forceinline__ RowSlot locate_row(const ChunkDev *__restrict__ chunks, const int *l_chunk,
-                                              const int *l_prefix, int n_list, int n_rows, int lr,
-                                              int *err)
-{
-    RowSlot s;
-    s.col = nullptr; s.val = nullptr; s.st = nullptr; s.len = 0;
-    s.y = 0.f; s.alpha = 0.f; s.q = 0.f; s.rw = 0.f;
-    if (lr < 0) return s;
-    if (lr >= n_rows) { atomicOr(err, ERR_PERM_RANGE); return s; }
-    const int j = find_chunk(l_prefix, n_list, lr);
-    const ChunkDev &ch = chunks[l_chunk[j]];
-    const int r = lr - l_prefix[j];
-    const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
-    const RowState st = ch.st[r];
-    s.q = st.q;
-    if (s.q == 0.f || e - b > GRAM_MAX_ROW) return s;
-    s.col = ch.col + b; s.val = ch.val + b; s.st = ch.st + r; s.len = e - b;
-    s.y = st.y; s.alpha = st.alpha; s.rw = st.rw;
-    return s;
-}
-
-// ------------------------------------------------------------------------------------------------
 // Workgroup-internal barrier among the helper wavefronts only (the chain wavefront keeps running).
 // cnt lives in LDS and only grows; target = arrivals expected so far.
 __device__ __forceinline__ void helper_barrier(int *cnt, int target)
