@@ -18,26 +18,34 @@ from typing import Callable, Dict, List, Optional, Sequence
 
 import numpy as np
 
-from .binding import ChicleRound, balance, projected_iteration_time
+from .binding import ChicleRound, balance, projected_iteration_time, scale_in, scale_out
 
 
 def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], list], target_rel: float,
                max_rounds: int, min_rounds: int = 0, table: Optional[np.ndarray] = None,
-               device: str = "cuda:0") -> Dict:
+               device: str = "cuda:0", schedule: Optional[Sequence] = None,
+               draws: Optional[Callable[[int, int], np.ndarray]] = None) -> Dict:
     """Rounds with a constant number of solvers K from alpha = 0, w = 0 until the duality gap has
     fallen to `target_rel` times its initial value (or `max_rounds`).
 
     permutations(round, rows_per_solver) supplies the visiting orders (they are inputs of the method).
     Returns the gap after every round (entry 0: before the first), the first round count at which the
     target was met (None if never), and the wall-clock time of the rounds up to that point (visiting
-    orders are uploaded before the clock starts)."""
+    orders are uploaded before the clock starts).
+
+    schedule: optional [(round, K), ...] changes of the number of solvers before the given rounds
+    (Section 2.2 cites that starting with many partitions and reducing them after a few iterations
+    speeds up convergence): fewer solvers through the scale-in policy, more through the scale-out policy
+    with draws(round, n_chunks) as its random words.  K is then the first entry's solver count."""
     import torch
-    g = ChicleRound.from_problem(problem, max_solvers=K, device=device)
+    changes = dict(schedule or [])
+    g = ChicleRound.from_problem(problem, max_solvers=max([K] + list(changes.values())), device=device)
     try:
         if table is None:
             table = balance(problem.chunk_nnz(), K)
         g.assign(K, table)
         rows = g.solver_rows()
+        ks = [K]
         g0 = g.gap()[2]
         gaps = [g0]
         reached, t_reached = None, None
@@ -45,7 +53,15 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
         elapsed = 0.0
         r = 0
         while r < max_rounds and (reached is None or r < min_rounds):
-            n_blk = min(block, max_rounds - r)
+            if r in changes and changes[r] != K:
+                K_new = changes[r]
+                table = scale_in(table, K, K_new) if K_new < K else \
+                    scale_out(table, K, K_new, draws(r, len(table)))
+                K = K_new
+                g.assign(K, table)
+                rows = g.solver_rows()
+            nxt = min([c for c in changes if c > r] or [max_rounds])
+            n_blk = min(block, max_rounds - r, nxt - r)
             dev = [g.upload_perm(permutations(r + i, rows)) for i in range(n_blk)]
             torch.cuda.synchronize()
             for i in range(n_blk):
@@ -55,12 +71,13 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
                 gap = g.gap()[2]                    # the scalars come back: the round has ended
                 elapsed += time.perf_counter() - t0
                 gaps.append(gap)
+                ks.append(K)
                 r += 1
                 if reached is None and gap <= target_rel * g0:
                     reached, t_reached = r, elapsed
                 if reached is not None and r >= min_rounds:
                     break
-        return {"K": K, "gaps": gaps, "rounds_to_target": reached, "seconds_to_target": t_reached,
+        return {"K": ks[0], "K_per_round": ks[1:], "gaps": gaps, "rounds_to_target": reached, "seconds_to_target": t_reached,
                 "seconds": elapsed, "rounds": r}
     finally:
         g.close()
@@ -93,6 +110,8 @@ def main(argv=None) -> int:
     ap.add_argument("--nodes", type=int, nargs="+", default=[16, 14, 8])
     ap.add_argument("--target", type=float, default=1e-3, help="gap relative to the initial gap")
     ap.add_argument("--max-rounds", type=int, default=200)
+    ap.add_argument("--schedule", nargs="*", default=[], metavar="ROUND:K",
+                    help="one more run that changes the number of solvers before the given rounds, e.g. 0:64 3:32 6:16")
     args = ap.parse_args(argv)
     cfg = get_config(args.workload, args.size)
     p = make_problem(cfg)
@@ -104,7 +123,18 @@ def main(argv=None) -> int:
               (K, args.target, res["rounds_to_target"], 1e3 * res["seconds"] / max(res["rounds"], 1),
                res["gaps"][-1]), file=sys.stderr, flush=True)
         results.append(res)
+    scheduled = None
+    if args.schedule:
+        from workloads import chunk_draws
+        sched = sorted(tuple(int(x) for x in item.split(":")) for item in args.schedule)
+        scheduled = run_to_gap(p, sched[0][1], lambda r, rows: round_permutations(cfg["seed"], r, rows), args.target,
+                               args.max_rounds, schedule=sched[1:],
+                               draws=lambda r, n: chunk_draws(cfg["seed"], r, n))
+        print("schedule %s: rounds to target %s, %.1f ms to target" %
+              (sched, scheduled["rounds_to_target"], 1e3 * (scheduled["seconds_to_target"] or float("nan"))),
+              file=sys.stderr, flush=True)
     out = {"workload": "%s/%s" % (args.workload, args.size), "target_rel": args.target,
+           "scheduled": None if scheduled is None else {k: v for k, v in scheduled.items() if k != "gaps"},
            "runs": [{k: v for k, v in r.items() if k != "gaps"} for r in results],
            "gaps": {str(r["K"]): r["gaps"] for r in results},
            "projection": project(results, args.nodes)}

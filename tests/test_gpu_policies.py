@@ -126,3 +126,32 @@ def test_microtask_emulation_run_matches_oracle(mods, K):
     rows = sweep.project([res], [K, 4])
     uni = [x for x in rows if x["mode"] == "uni-tasks"]
     assert len(uni) == 1 and uni[0]["iteration_time"] == pytest.approx(16.0 / K)
+
+
+def test_scale_in_schedule_run_matches_oracle(mods):
+    """Many solvers first, fewer after a few rounds (the schedule Section 2.2 cites): the driver's run,
+    with its tables from the library's scale-in policy, against the oracle under the oracle's tables."""
+    oracle_mod, binding = mods
+    from paper_1909_04885_amd import sweep
+    cfg, p = cached_problem("sparse_zipf", "mini")
+    print("\ncase sparse_zipf mini, schedule 6 -> 3 -> 2", flush=True)
+    sched, rounds = [(3, 3), (6, 2)], 9
+    res = sweep.run_to_gap(p, 6, lambda r, rows: round_permutations(cfg["seed"], r, rows), 1e-9,
+                           max_rounds=rounds, schedule=sched)
+    assert res["K_per_round"] == [6, 6, 6, 3, 3, 3, 2, 2, 2]
+    o = oracle_mod.OracleCoCoA.from_problem(p)
+    K, table = 6, oracle_mod.assign_greedy(p.chunk_nnz(), 6).tolist()
+    o.assign(K, np.asarray(table, dtype=np.int32))
+    ref = [o.gap()[2]]
+    for r in range(rounds):
+        if r in dict(sched):
+            K_new = dict(sched)[r]
+            table = opol.scale_in(table, K, K_new)
+            K = K_new
+            o.assign(K, np.asarray(table, dtype=np.int32))
+        o.local_epoch(round_permutations(cfg["seed"], r, o.rows_per_solver()))
+        o.aggregate()
+        ref.append(o.gap()[2])
+    print("gaps", ["%.4f" % x for x in res["gaps"]], flush=True)
+    for a, b in zip(res["gaps"], ref):
+        assert abs(a - b) <= 1e-3 * abs(b)
