@@ -152,6 +152,7 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
 // only the rare columns go to the cache hierarchy.  1024 threads; dynamic LDS = n_hot * sizeof(WT).
 constexpr int GAP_HOT_THREADS = 1024;
 constexpr int GAP_HOT_BYTES = 48 * 1024;
+constexpr int GAP_HOT_UNROLL = 3;
 
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkDev *__restrict__ chunks,
@@ -180,17 +181,28 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
         const int b0 = rp[r0], e0 = rp[r0 + 1];
         const int b1 = two ? rp[r1] : 0, e1 = two ? rp[r1 + 1] : 0;
         WT z0 = 0, z1 = 0;
-        int p0 = b0 + sub, p1 = b1 + sub;
-        while (p0 < e0 || p1 < e1) {
-            int c0 = 0, c1 = 0;
-            float v0 = 0.f, v1 = 0.f;
-            if (p0 < e0) { c0 = col[p0]; v0 = val[p0]; }
-            if (p1 < e1) { c1 = col[p1]; v1 = val[p1]; }
-            const WT w0 = c0 < n_hot ? hot[c0] : w[c0];
-            const WT w1 = c1 < n_hot ? hot[c1] : w[c1];
-            z0 += (WT)v0 * w0;
-            z1 += (WT)v1 * w1;
-            p0 += LPR; p1 += LPR;
+        // GAP_HOT_UNROLL segments of each row per trip, all entry loads issued before the first gather:
+        // a short row costs one trip to memory for its entries and one for the rare columns of w
+        for (int p0 = b0 + sub, p1 = b1 + sub; p0 < e0 || p1 < e1; p0 += GAP_HOT_UNROLL * LPR, p1 += GAP_HOT_UNROLL * LPR) {
+            int c0[GAP_HOT_UNROLL], c1[GAP_HOT_UNROLL];
+            float v0[GAP_HOT_UNROLL], v1[GAP_HOT_UNROLL];
+#pragma unroll
+            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
+                c0[k] = 0; c1[k] = 0; v0[k] = 0.f; v1[k] = 0.f;
+                if (p0 + k * LPR < e0) { c0[k] = col[p0 + k * LPR]; v0[k] = val[p0 + k * LPR]; }
+                if (p1 + k * LPR < e1) { c1[k] = col[p1 + k * LPR]; v1[k] = val[p1 + k * LPR]; }
+            }
+            WT w0[GAP_HOT_UNROLL], w1[GAP_HOT_UNROLL];
+#pragma unroll
+            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
+                w0[k] = c0[k] < n_hot ? hot[c0[k]] : w[c0[k]];
+                w1[k] = c1[k] < n_hot ? hot[c1[k]] : w[c1[k]];
+            }
+#pragma unroll
+            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
+                z0 += (WT)v0[k] * w0[k];
+                z1 += (WT)v1[k] * w1[k];
+            }
         }
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) { z0 += __shfl_xor(z0, o, 64); z1 += __shfl_xor(z1, o, 64); }
