@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "device_types.hpp"
+#include "mem.hpp"
 #include "sdca_rowwise.hpp"
 
 namespace chicle {
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
 // only the rare columns go to the cache hierarchy.  1024 threads; dynamic LDS = n_hot * sizeof(WT).
 constexpr int GAP_HOT_THREADS = 1024;
 constexpr int GAP_HOT_BYTES = 48 * 1024;
-constexpr int GAP_HOT_UNROLL = 3;
+constexpr int GAP_HOT_LPR = 16;             // lanes per row; a lane takes 4 consecutive entries
 
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkDev *__restrict__ chunks,
@@ -181,25 +182,27 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
         const int b0 = rp[r0], e0 = rp[r0 + 1];
         const int b1 = two ? rp[r1] : 0, e1 = two ? rp[r1 + 1] : 0;
         WT z0 = 0, z1 = 0;
-        // GAP_HOT_UNROLL segments of each row per trip, all entry loads issued before the first gather:
-        // a short row costs one trip to memory for its entries and one for the rare columns of w
-        for (int p0 = b0 + sub, p1 = b1 + sub; p0 < e0 || p1 < e1; p0 += GAP_HOT_UNROLL * LPR, p1 += GAP_HOT_UNROLL * LPR) {
-            int c0[GAP_HOT_UNROLL], c1[GAP_HOT_UNROLL];
-            float v0[GAP_HOT_UNROLL], v1[GAP_HOT_UNROLL];
+        // Each lane takes 4 consecutive entries of its row with one 16-byte load per array (the vector
+        // memory pipeline is busy per instruction, not per byte, here); rows are at most 4 * LPR long where
+        // this kernel is used, and every chunk's arrays are followed by readable slack.
+        {
+            const int p0 = b0 + 4 * sub, p1 = b1 + 4 * sub;
+            int4_a4 c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
+            float4_a4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+            if (p0 < e0) { c0 = gld4(col + p0); v0 = gld4(val + p0); }
+            if (p1 < e1) { c1 = gld4(col + p1); v1 = gld4(val + p1); }
+            WT w0[4], w1[4];
 #pragma unroll
-            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
-                c0[k] = 0; c1[k] = 0; v0[k] = 0.f; v1[k] = 0.f;
-                if (p0 + k * LPR < e0) { c0[k] = col[p0 + k * LPR]; v0[k] = val[p0 + k * LPR]; }
-                if (p1 + k * LPR < e1) { c1[k] = col[p1 + k * LPR]; v1[k] = val[p1 + k * LPR]; }
+            for (int k = 0; k < 4; ++k) {
+                const bool in0 = p0 + k < e0, in1 = p1 + k < e1;
+                const int a0 = in0 ? c0[k] : 0, a1 = in1 ? c1[k] : 0;
+                w0[k] = a0 < n_hot ? hot[a0] : w[a0];
+                w1[k] = a1 < n_hot ? hot[a1] : w[a1];
+                if (!in0) v0[k] = 0.f;
+                if (!in1) v1[k] = 0.f;
             }
-            WT w0[GAP_HOT_UNROLL], w1[GAP_HOT_UNROLL];
 #pragma unroll
-            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
-                w0[k] = c0[k] < n_hot ? hot[c0[k]] : w[c0[k]];
-                w1[k] = c1[k] < n_hot ? hot[c1[k]] : w[c1[k]];
-            }
-#pragma unroll
-            for (int k = 0; k < GAP_HOT_UNROLL; ++k) {
+            for (int k = 0; k < 4; ++k) {
                 z0 += (WT)v0[k] * w0[k];
                 z1 += (WT)v1[k] * w1[k];
             }

@@ -360,7 +360,7 @@ void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w)
     const dim3 grid(grid_x, c->n_chunks);
     if (c->gap_hot_grid > 0) {
         const int n_hot = (int)std::min<int64_t>(c->d, GAP_HOT_BYTES / (int)sizeof(WT));
-        hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, LPRG, WT>), dim3(c->gap_hot_grid, c->n_chunks),
+        hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, GAP_HOT_LPR, WT>), dim3(c->gap_hot_grid, c->n_chunks),
                            dim3(GAP_HOT_THREADS), n_hot * sizeof(WT), c->stream, c->chunks_dev, w, n_hot,
                            c->part_loss, c->part_conj);
     } else if (c->dense)
@@ -403,8 +403,8 @@ int run_row_pass(chicle_ctx *c, int *grid_out)
     gx = std::max(1, std::min(gx, c->gap_parts / c->n_chunks));
     // popularity-numbered columns: frequent part of w from LDS, few large workgroups per chunk
     c->gap_hot_grid = 0;
-    if (c->renumbered && !c->dense && c->gap_lpr <= 16) {
-        const int rows_per_hot_wg = 2 * (GAP_HOT_THREADS / c->gap_lpr);
+    if (c->renumbered && !c->dense && c->max_row_len <= 4 * GAP_HOT_LPR) {
+        const int rows_per_hot_wg = 2 * (GAP_HOT_THREADS / GAP_HOT_LPR);
         gx = std::max(1, std::min(std::min(2, (max_rows + rows_per_hot_wg - 1) / rows_per_hot_wg),
                                   c->gap_parts / c->n_chunks));
         c->gap_hot_grid = gx;
