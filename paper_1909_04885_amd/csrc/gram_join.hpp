@@ -35,9 +35,18 @@ struct GramRows {                                     // the 128 rows of a windo
     float scale[BATCH];
 };
 
+// The accumulators are doubles: the join adds into them with LDS atomics, and on this hardware those run
+// at the rate of the LDS pipeline for doubles while they are serialised lane by lane for floats.  The
+// dense slab A is only alive from the clearing of the tables to the end of the dense product, when G is
+// not; it occupies the tail of G's storage.
 struct GramShared {
-    float G[TILE_W][G_LD];                 // accumulators [jp][i]
-    float A[GRAM_DENSE][TILE_W];           // dense part, [column][window row]
+    union {
+        double G[TILE_W][G_LD];            // accumulators [jp][i]
+        struct {
+            unsigned char before_A[sizeof(double) * TILE_W * G_LD - sizeof(float) * GRAM_DENSE * TILE_W];
+            float A[GRAM_DENSE][TILE_W];   // dense part, [column][window row]
+        } d;
+    };
     int keys[GRAM_SLOTS];                  // column per slot during insertion, then fill cursors
     unsigned short start[GRAM_SLOTS];      // entries per slot, then exclusive scan = list begin
     float post_val[GRAM_ENTRIES];          // posting lists grouped by slot: value ...
@@ -148,7 +157,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
         }
         lookup1(tile + 1);
         for (int i = tid; i < GRAM_SLOTS; i += GRAM_THREADS) { sh.keys[i] = EMPTY_KEY; sh.start[i] = 0; }
-        for (int i = tid; i < GRAM_DENSE * TILE_W; i += GRAM_THREADS) (&sh.A[0][0])[i] = 0.f;
+        for (int i = tid; i < GRAM_DENSE * TILE_W; i += GRAM_THREADS) (&sh.d.A[0][0])[i] = 0.f;
         __syncthreads();
 
         // ---- dense part into A, the rest into the hash table (count per slot)
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
             const int s = idx / GRAM_MAX_ROW;
             e_slot[k] = -1; first[k] = EMPTY_KEY;
             if (e_live[k]) {
-                if (e_col[k] < GRAM_DENSE) sh.A[e_col[k]][s] = e_val[k];
+                if (e_col[k] < GRAM_DENSE) sh.d.A[e_col[k]][s] = e_val[k];
                 else {
                     e_slot[k] = gram_hash(e_col[k]);
                     first[k] = atomicCAS(&sh.keys[e_slot[k]], EMPTY_KEY, e_col[k]);
@@ -221,17 +230,18 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
             float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll 8
             for (int h = 0; h < GRAM_DENSE; ++h) {
-                const float4 ai = *reinterpret_cast<const float4 *>(&sh.A[h][BATCH + i0]);
-                const float2 aj = *reinterpret_cast<const float2 *>(&sh.A[h][j0]);
+                const float4 ai = *reinterpret_cast<const float4 *>(&sh.d.A[h][BATCH + i0]);
+                const float2 aj = *reinterpret_cast<const float2 *>(&sh.d.A[h][j0]);
                 acc[0][0] += aj.x * ai.x; acc[0][1] += aj.x * ai.y; acc[0][2] += aj.x * ai.z; acc[0][3] += aj.x * ai.w;
                 acc[1][0] += aj.y * ai.x; acc[1][1] += aj.y * ai.y; acc[1][2] += aj.y * ai.z; acc[1][3] += aj.y * ai.w;
             }
+            lookup4();
+            __syncthreads();                 // every read of A is done: G may take its place
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) sh.G[j0 + a][i0 + b] = acc[a][b];
+                for (int b = 0; b < 4; ++b) sh.G[j0 + a][i0 + b] = (double)acc[a][b];
         }
-        lookup4();
         __syncthreads();
 
         // ---- sparse part: every entry of a block row meets the other members of its column's list
@@ -251,7 +261,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (p + j < pe && (sf[j] < BATCH || sf[j] - BATCH < i)) atomicAdd(&sh.G[sf[j]][i], a * vf[j]);
+                    if (p + j < pe && (sf[j] < BATCH || sf[j] - BATCH < i)) atomicAdd(&sh.G[sf[j]][i], (double)(a * vf[j]));
             }
         }
         publish(sh.rows[(tile + 1 - t_begin) & 1]);
@@ -262,10 +272,10 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
         for (int idx = tid; idx < TILE_FLOATS; idx += GRAM_THREADS) {
             const int jp = idx >> 6, i = idx & 63;
             float g = 0.f;
-            if (jp < BATCH || jp - BATCH < i) g = sh.G[jp][i] * R.scale[i] * R.sgn[BATCH + i] * R.sgn[jp];
+            if (jp < BATCH || jp - BATCH < i) g = (float)sh.G[jp][i] * R.scale[i] * R.sgn[BATCH + i] * R.sgn[jp];
             out[idx] = g;
         }
-        // the next iteration's first barrier separates this read of G and R from their next writes
+        __syncthreads();     // G has been read: the next tile may clear A, which lies inside it
     }
 }
 
