@@ -22,7 +22,7 @@ _SRC = os.path.join(_HERE, "cocoa_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-_LOSS = {"hinge": 0, "squared": 1}
+_LOSS = {"hinge": 0, "squared": 1, "logistic": 2}
 
 
 def build_oracle(force: bool = False) -> str:

@@ -17,6 +17,9 @@
  *        D(a) = -lambda/2 |w(a)|^2 - 1/n sum_i loss_i^*(-a_i),   w(a) = 1/(lambda n) sum_i a_i s_i x_i
  * with   hinge:   loss_i(z) = max(0, 1 - y_i z),  s_i = y_i,  a_i in [0,1],  -loss_i^*(-a_i) = a_i
  *        squared: loss_i(z) = (z - y_i)^2 / 2,     s_i = 1,    a_i real,     loss_i^*(-a_i) = a_i^2/2 - a_i y_i
+ *        logistic: loss_i(z) = log(1 + exp(-y_i z)), s_i = y_i,  a_i in [0,1],
+ *                  loss_i^*(-a_i) = a_i log a_i + (1 - a_i) log(1 - a_i)   (0 log 0 = 0)
+ * (Section 2.2 speaks of generalised linear models in general; the evaluation trains the hinge case.)
  * and the "adding" combination (gamma = 1) that sigma = K makes safe.
  *
  * All state (a, w, v) is double; data (values, labels) are the caller's float arrays.
@@ -25,7 +28,7 @@
 #include <stddef.h>
 #include <math.h>
 
-enum { ORACLE_HINGE = 0, ORACLE_SQUARED = 1 };
+enum { ORACLE_HINGE = 0, ORACLE_SQUARED = 1, ORACLE_LOGISTIC = 2 };
 
 /* One exact coordinate step of the local subproblem.
  * z = x_i . v where v = w + sigma * (Delta w_k so far); q = |x_i|^2; c = lambda n / sigma.
@@ -39,8 +42,27 @@ static double dual_step(int loss, double a, double y, double z, double q, double
         if (a_new > 1.0) a_new = 1.0;
         return a_new - a;
     }
+    if (loss == ORACLE_LOGISTIC) {
+        /* a' = a + delta maximises H(a') - (a' - a) y z - (q / 2c) (a' - a)^2 with the entropy
+         * H(a') = -a' log a' - (1 - a') log(1 - a').  With a' = 1 / (1 + exp(-s)) the stationarity
+         * condition reads f(s) = -s - y z - (q/c) (a'(s) - a) = 0; f decreases strictly and its root
+         * lies within q/c of -y z because |a' - a| <= 1.  Plain bisection. */
+        const double r = q / c, m = -y * z;
+        double lo = m - r, hi = m + r;
+        for (int it = 0; it < 200; ++it) {
+            const double s = 0.5 * (lo + hi);
+            const double ap = s >= 0.0 ? 1.0 / (1.0 + exp(-s)) : exp(s) / (1.0 + exp(s));
+            const double f = -s + m - r * (ap - a);
+            if (f > 0.0) lo = s; else hi = s;
+        }
+        const double s = 0.5 * (lo + hi);
+        const double ap = s >= 0.0 ? 1.0 / (1.0 + exp(-s)) : exp(s) / (1.0 + exp(s));
+        return ap - a;
+    }
     return (y - z - a) / (1.0 + q / c);
 }
+
+static double xlogx(double x) { return x > 0.0 ? x * log(x) : 0.0; }
 
 /* Local solver of one worker, sparse rows (Section 2.2: sequential coordinate steps, one pass).
  *   rows[t]      global row id of the worker's t-th local row (t = 0 .. n_local-1)
@@ -67,7 +89,7 @@ void oracle_local_epoch_csr(int loss, int64_t n_local, const int64_t *rows, cons
         if (q == 0.0) continue;
         const double delta = dual_step(loss, alpha[i], (double)y[i], z, q, c);
         alpha[i] += delta;
-        const double s = (loss == ORACLE_HINGE) ? (double)y[i] : 1.0;
+        const double s = (loss == ORACLE_SQUARED) ? 1.0 : (double)y[i];
         const double coef = delta * s / c;
         for (int64_t p = b; p < e; ++p) v[col[p]] += coef * (double)val[p];
     }
@@ -90,7 +112,7 @@ void oracle_local_epoch_dense(int loss, int64_t n_local, const int64_t *rows, co
         if (q == 0.0) continue;
         const double delta = dual_step(loss, alpha[i], (double)y[i], z, q, c);
         alpha[i] += delta;
-        const double s = (loss == ORACLE_HINGE) ? (double)y[i] : 1.0;
+        const double s = (loss == ORACLE_SQUARED) ? 1.0 : (double)y[i];
         const double coef = delta * s / c;
         for (int64_t j = 0; j < d; ++j) v[j] += coef * (double)x[j];
     }
@@ -99,7 +121,8 @@ void oracle_local_epoch_dense(int loss, int64_t n_local, const int64_t *rows, co
 /* Primal value, dual value and their difference at (w, alpha); also the per-row
  * Fenchel-Young form of the gap, which equals P - D whenever w = w(alpha).
  *   out[0] = P, out[1] = D, out[2] = P - D, out[3] = 1/n sum_i g_i
- * with hinge g_i = max(0, 1 - y_i z_i) - a_i + a_i y_i z_i and squared g_i = (z_i - y_i + a_i)^2 / 2.
+ * with hinge g_i = max(0, 1 - y_i z_i) - a_i + a_i y_i z_i, squared g_i = (z_i - y_i + a_i)^2 / 2 and
+ * logistic g_i = log(1 + exp(-y_i z_i)) + a_i log a_i + (1 - a_i) log(1 - a_i) + a_i y_i z_i.
  * Pass X != NULL for dense rows, else the CSR arrays. */
 void oracle_gap(int loss, int64_t n_total, int64_t d, const float *X, const int64_t *row_ptr,
                 const int32_t *col, const float *val, const float *y, const double *alpha,
@@ -123,6 +146,13 @@ void oracle_gap(int loss, int64_t n_total, int64_t d, const float *X, const int6
             loss_sum += l;
             conj_sum += -a;                      /* loss^*(-a) = -a on [0,1] */
             fy_sum += l - a + a * yi * z;
+        } else if (loss == ORACLE_LOGISTIC) {
+            const double m = -yi * z;
+            const double l = m > 0.0 ? m + log1p(exp(-m)) : log1p(exp(m));
+            const double cj = xlogx(a) + xlogx(1.0 - a);
+            loss_sum += l;
+            conj_sum += cj;
+            fy_sum += l + cj + a * yi * z;
         } else {
             const double r = z - yi;
             loss_sum += 0.5 * r * r;

@@ -22,7 +22,7 @@ from workloads.configs import k_for_round
 def tiny_dense(n, d, seed, loss, separable=False):
     g = np.random.default_rng(seed)
     X = g.standard_normal((n, d)).astype(np.float32)
-    if loss == "hinge":
+    if loss in ("hinge", "logistic"):
         wst = g.standard_normal(d)
         y = np.where(X.astype(np.float64) @ wst >= 0, 1.0, -1.0)
         if not separable:
@@ -49,7 +49,11 @@ def bounds(n, rows):
 
 
 def s_vec(loss, y):
-    return y.astype(np.float64) if loss == "hinge" else np.ones(len(y))
+    return np.ones(len(y)) if loss == "squared" else y.astype(np.float64)
+
+
+def xlogx(a):
+    return np.where(a > 0, a * np.log(np.where(a > 0, a, 1.0)), 0.0)
 
 
 def w_of_alpha(loss, X, y, alpha, lam):
@@ -61,6 +65,8 @@ def primal(loss, X, y, w, lam):
     z = X.astype(np.float64) @ w
     if loss == "hinge":
         l = np.maximum(0.0, 1.0 - y * z)
+    elif loss == "logistic":
+        l = np.logaddexp(0.0, -y * z)
     else:
         l = 0.5 * (z - y) ** 2
     return 0.5 * lam * w @ w + l.mean()
@@ -72,6 +78,11 @@ def dual(loss, X, y, alpha, lam):
         if np.any(alpha < -1e-15) or np.any(alpha > 1 + 1e-15):
             return -np.inf
         return alpha.mean() - 0.5 * lam * w @ w
+    if loss == "logistic":
+        if np.any(alpha < -1e-15) or np.any(alpha > 1 + 1e-15):
+            return -np.inf
+        a = np.clip(alpha, 0.0, 1.0)
+        return -(xlogx(a) + xlogx(1.0 - a)).mean() - 0.5 * lam * w @ w
     return -(0.5 * alpha ** 2 - alpha * y).mean() - 0.5 * lam * w @ w
 
 
@@ -103,10 +114,15 @@ def test_gap_at_zero(oracle_mod, sparse):
     P, D, G, FY = o.gap()
     want = 0.5 * np.mean(y.astype(np.float64) ** 2)
     assert D == 0.0 and abs(P - want) < 1e-14 and abs(G - want) < 1e-14 and abs(FY - want) < 1e-14
+    X, y = tiny_dense(50, 7, 3, "logistic")
+    kw = dict(zip(("row_ptr", "col", "val"), to_csr(X))) if sparse else dict(X=X)
+    o = oracle_mod.OracleCoCoA("logistic", 50, 7, 0.01, y, bounds(50, 16), **kw)
+    P, D, G, FY = o.gap()
+    assert D == 0.0 and abs(P - np.log(2.0)) < 1e-14 and abs(G - np.log(2.0)) < 1e-14 and abs(FY - np.log(2.0)) < 1e-14
 
 
 # ----------------------------------------------------------------------------- P2, P3, P4, P6
-@pytest.mark.parametrize("loss", ["hinge", "squared"])
+@pytest.mark.parametrize("loss", ["hinge", "squared", "logistic"])
 @pytest.mark.parametrize("sparse", [False, True])
 @pytest.mark.parametrize("K", [1, 3, 5])
 def test_invariants_every_round(oracle_mod, loss, sparse, K):
@@ -135,7 +151,7 @@ def test_invariants_every_round(oracle_mod, loss, sparse, K):
         # P6: sigma = K with adding never decreases the dual
         assert D >= prevD - 1e-13
         prevD = D
-        if loss == "hinge":
+        if loss in ("hinge", "logistic"):
             assert o.alpha.min() >= 0.0 and o.alpha.max() <= 1.0
         assert o.alpha[7] == 0.0
 
@@ -185,12 +201,16 @@ def _subproblem_value(loss, X, y, alpha, w, rows_k, dalpha_k, lam, sigma):
         if np.any(a < 0) or np.any(a > 1):
             return -np.inf
         conj = -a
+    elif loss == "logistic":
+        if np.any(a < 0) or np.any(a > 1):
+            return -np.inf
+        conj = xlogx(a) + xlogx(1.0 - a)
     else:
         conj = 0.5 * a * a - a * y[rows_k]
     return -conj.sum() / n - (w @ u) / n - 0.5 * lam * sigma * (u @ u) / (lam * n) ** 2
 
 
-@pytest.mark.parametrize("loss", ["hinge", "squared"])
+@pytest.mark.parametrize("loss", ["hinge", "squared", "logistic"])
 def test_single_step_is_argmax_of_local_objective(oracle_mod, loss):
     from oracle.cocoa import _load, _p
     L = _load()
@@ -200,14 +220,16 @@ def test_single_step_is_argmax_of_local_objective(oracle_mod, loss):
     rp, col, val = to_csr(X)
     rows_k = np.array([1, 4, 6, 9], dtype=np.int64)
     for trial in range(24):
-        alpha = g.random(n) if loss == "hinge" else g.standard_normal(n)
-        if loss == "hinge" and trial % 3 == 0:
+        boxed = loss in ("hinge", "logistic")
+        code = {"hinge": 0, "squared": 1, "logistic": 2}[loss]
+        alpha = g.random(n) if boxed else g.standard_normal(n)
+        if boxed and trial % 3 == 0:
             alpha[rows_k] = g.integers(0, 2, size=rows_k.size).astype(np.float64)  # at the bounds
         w = g.standard_normal(d) * (3.0 if trial % 2 else 0.2)
         dalpha = np.zeros(rows_k.size)
         # some progress already made inside this pass
         dalpha[1:] = 0.1 * g.standard_normal(rows_k.size - 1)
-        if loss == "hinge":
+        if boxed:
             dalpha = np.clip(alpha[rows_k] + dalpha, 0, 1) - alpha[rows_k]
         dalpha[0] = 0.0
         a_now = alpha.copy()
@@ -220,10 +242,10 @@ def test_single_step_is_argmax_of_local_objective(oracle_mod, loss):
         for sparse in (True, False):
             a_call, v_call = a_now.copy(), v.copy()
             if sparse:
-                L.oracle_local_epoch_csr(0 if loss == "hinge" else 1, 1, _p(one), _p(zero), _p(rp), _p(col),
+                L.oracle_local_epoch_csr(code, 1, _p(one), _p(zero), _p(rp), _p(col),
                                          _p(val), _p(y), _p(a_call), _p(v_call), lam, n, sigma)
             else:
-                L.oracle_local_epoch_dense(0 if loss == "hinge" else 1, 1, _p(one), _p(zero), _p(X), d,
+                L.oracle_local_epoch_dense(code, 1, _p(one), _p(zero), _p(X), d,
                                            _p(y), _p(a_call), _p(v_call), lam, n, sigma)
             delta = a_call[rows_k[0]] - a_now[rows_k[0]]
             # only that row's dual variable moved, and v moved along s_i x_i by sigma*delta/(lam n)
@@ -237,7 +259,7 @@ def test_single_step_is_argmax_of_local_objective(oracle_mod, loss):
                 da[0] = dl
                 return _subproblem_value(loss, X, y, alpha, w, rows_k, da, lam, sigma)
 
-            if loss == "hinge":
+            if boxed:
                 lo, hi = -alpha[rows_k[0]], 1.0 - alpha[rows_k[0]]
             else:
                 lo, hi = delta - 5.0, delta + 5.0
@@ -304,7 +326,7 @@ def test_separable_gap_goes_to_zero(oracle_mod):
 
 
 # ----------------------------------------------------------------------------- safe aggregation
-@pytest.mark.parametrize("loss", ["hinge", "squared"])
+@pytest.mark.parametrize("loss", ["hinge", "squared", "logistic"])
 def test_sum_of_local_objectives_bounds_the_dual(oracle_mod, loss):
     """With sigma = K and adding, D(alpha + sum_k dalpha_k) >= sum_k G_k(dalpha_k), where G_k carries
     the 1/K share of -lam/2 |w|^2 (the separable lower bound CoCoA maximises)."""
@@ -328,6 +350,31 @@ def test_sum_of_local_objectives_bounds_the_dual(oracle_mod, loss):
             z = np.zeros(rk.size)
             assert _subproblem_value(loss, X, y, a0, w0, rk, o.alpha[rk] - a0[rk], lam, float(K)) >= \
                 _subproblem_value(loss, X, y, a0, w0, rk, z, lam, float(K)) - 1e-14
+
+
+@pytest.mark.parametrize("K", [1, 3])
+def test_logistic_reaches_the_primal_optimum(oracle_mod, K):
+    """Regularised logistic regression has a smooth primal: a library quasi-Newton method on P(w) gives
+    w* to high accuracy; the oracle's rounds must close the gap and arrive at the same w and P."""
+    n, d, lam = 150, 6, 0.05
+    X, y = tiny_dense(n, d, 21, "logistic")
+    o = oracle_mod.OracleCoCoA("logistic", n, d, lam, y, bounds(n, 25), X=X)
+    hist = run_rounds(o, K, 120 if K == 1 else 400)
+    Xd, yd = X.astype(np.float64), y.astype(np.float64)
+
+    def f(w):
+        z = Xd @ w
+        val = 0.5 * lam * w @ w + np.logaddexp(0.0, -yd * z).mean()
+        grad = lam * w - Xd.T @ (yd / (1.0 + np.exp(yd * z))) / n
+        return val, grad
+
+    res = scipy.optimize.minimize(f, np.zeros(d), jac=True, method="L-BFGS-B",
+                                  options={"ftol": 1e-15, "gtol": 1e-12, "maxiter": 2000})
+    P, D, G, FY = hist[-1]
+    assert G < 1e-8 and abs(P - res.fun) < 1e-8
+    assert np.linalg.norm(o.w - res.x) < 1e-4 * max(1.0, np.linalg.norm(res.x))
+    # at the optimum the dual variables are the loss derivatives: a_i = 1 / (1 + exp(y_i x_i.w))
+    assert np.max(np.abs(o.alpha - 1.0 / (1.0 + np.exp(yd * (Xd @ res.x))))) < 1e-3
 
 
 def test_delta_w_is_image_of_delta_alpha(oracle_mod):
