@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--workload", default="sparse_zipf")
     ap.add_argument("--size", default="full")
     ap.add_argument("--solver", default="auto")
+    ap.add_argument("--loss", default=None, choices=["hinge", "squared", "logistic"],
+                    help="train this loss on the workload's data instead of its own (labels must fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-time-to-gap", action="store_true")
     ap.add_argument("--gap-round-cap", type=int, default=100)
@@ -90,6 +92,9 @@ def main():
     t0 = time.time()
     p = make_problem(cfg)
     K = cfg["K"]
+    if args.loss and args.loss != p.loss:
+        import dataclasses
+        p = dataclasses.replace(p, loss=args.loss)
     table = chicle.balance(p.chunk_nnz(), K)
     print("generated %s/%s: n=%d d=%d entries=%d chunks=%d K=%d in %.1fs" %
           (args.workload, args.size, p.n, p.d, p.nnz, p.n_chunks, K, time.time() - t0), file=sys.stderr, flush=True)

@@ -13,6 +13,8 @@
  *                   D(a) = -lambda/2 |w(a)|^2 - 1/n sum_i loss_i^*(-a_i),  w(a) = 1/(lambda n) sum_i a_i s_i x_i
  *   hinge   : loss_i(z) = max(0, 1 - y_i z), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]
  *   squared : loss_i(z) = (z - y_i)^2 / 2,  s_i = 1,  a_i real
+ *   logistic: loss_i(z) = log(1 + exp(-y_i z)), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]; its coordinate
+ *             step has no closed form (a safeguarded Newton iteration), so it always uses the row-wise solver
  *
  * Data live in HBM as chunks (Section 3 "Uni-tasks", Section 4.4 "In-memory chunk data
  * format"): a chunk is one contiguous block holding a run of rows (CSR or dense) together with
@@ -59,7 +61,7 @@ enum chicle_status {
     CHICLE_EDEVICE = -4   /* HIP error, or a kernel flagged bad input (e.g. perm entry out of range) */
 };
 
-enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1 };
+enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1, CHICLE_LOSS_LOGISTIC = 2 };
 
 /* Which local-solver kernel chicle_local_epoch launches (both visit the coordinates in exactly the
  * given order; they differ only in floating-point summation order). */
@@ -102,10 +104,10 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
 /* Copy one chunk into the chunk store (Section 4.4).  All pointers are host arrays.
  *   row_ptr  n_rows+1 chunk-local offsets, row_ptr[0] = 0, non-decreasing
  *   col      row_ptr[n_rows] column ids in [0, d), strictly ascending inside a row
- *   val      matching values;  y  n_rows labels (+-1 for hinge) or targets
- *   alpha0   initial dual variables or NULL for zeros (hinge: must lie in [0,1])
+ *   val      matching values;  y  n_rows labels (+-1 for hinge and logistic) or targets
+ *   alpha0   initial dual variables or NULL for zeros (hinge, logistic: must lie in [0,1])
  * Legal in LOADING only.  Errors: EINVAL (malformed arrays, id out of range or already loaded,
- * hinge label not +-1), ENOMEM (store full), ESTATE. */
+ * label not +-1 where the loss asks for it), ENOMEM (store full), ESTATE. */
 int chicle_load_chunk_csr(chicle_ctx *ctx, int32_t chunk_id, int32_t n_rows, const int32_t *row_ptr,
                           const int32_t *col, const float *val, const float *y, const float *alpha0);
 

@@ -87,6 +87,7 @@ __device__ __forceinline__ void block_sum2_store(double a, double b, double *out
 // conjugate sum) in double.
 //   hinge   : loss = max(0, 1 - y z),   conj = loss^*(-a) = -a
 //   squared : loss = (z - y)^2 / 2,     conj = a^2/2 - a y
+//   logistic: loss = log(1 + exp(-y z)), conj = a log a + (1 - a) log(1 - a); rw = -y z
 template <int LOSS, typename WT>
 __device__ __forceinline__ void gap_row_terms(RowState *st, WT z, double &s_loss, double &s_conj)
 {
@@ -96,6 +97,12 @@ __device__ __forceinline__ void gap_row_terms(RowState *st, WT z, double &s_loss
         st->rw = (float)rw;
         s_loss += (double)(rw > (WT)0 ? rw : (WT)0);
         s_conj += (double)(-a);
+    } else if (LOSS == 2) {
+        const double m = -(double)y * (double)z;
+        st->rw = (float)m;
+        s_loss += fmax(m, 0.0) + log1p(exp(-fabs(m)));
+        const double ad = (double)a, bd = 1.0 - (double)a;
+        s_conj += (ad > 0.0 ? ad * log(ad) : 0.0) + (bd > 0.0 ? bd * log(bd) : 0.0);
     } else {
         const WT rw = (WT)y - z;
         st->rw = (float)rw;

@@ -240,7 +240,9 @@ bool dense_as_csr(int32_t d) { return d <= GRAM_MAX_ROW; }
 
 bool batched_eligible(const chicle_ctx *c)
 {
-    return !c->dense && c->max_row_len <= GRAM_MAX_ROW && c->max_list <= BATCHED_MAX_LIST;
+    // (the blocked recurrence needs the step in closed form: hinge and squared loss)
+    return c->loss != CHICLE_LOSS_LOGISTIC && !c->dense && c->max_row_len <= GRAM_MAX_ROW &&
+           c->max_list <= BATCHED_MAX_LIST;
 }
 
 template <int LOSS>
@@ -372,11 +374,12 @@ void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w)
 }
 
 // Squared loss: dot products in double against the double w (its steps cancel y - z - alpha down to the
-// size of the update); hinge: float against the float mirror.
+// size of the update); logistic: in double as well (loss and conjugate nearly cancel in the gap close to
+// the optimum); hinge: float against the float mirror.
 template <int LOSS, int LPRG>
 void launch_gap_rows(chicle_ctx *c, int grid)
 {
-    if (LOSS == 1) launch_gap_rows_t<LOSS, LPRG, double>(c, grid, c->w64);
+    if (LOSS != 0) launch_gap_rows_t<LOSS, LPRG, double>(c, grid, c->w64);
     else launch_gap_rows_t<LOSS, LPRG, float>(c, grid, c->w);
 }
 
@@ -409,7 +412,9 @@ int run_row_pass(chicle_ctx *c, int *grid_out)
                                   c->gap_parts / c->n_chunks));
         c->gap_hot_grid = gx;
     }
-    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx); else launch_gap_lpr<1>(c, gx);
+    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx);
+    else if (c->loss == CHICLE_LOSS_SQUARED) launch_gap_lpr<1>(c, gx);
+    else launch_gap_lpr<2>(c, gx);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = true;
     if (grid_out) *grid_out = gx * c->n_chunks;
@@ -495,7 +500,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
 {
     if (!out) return CHICLE_EINVAL;
     *out = nullptr;
-    if ((loss != CHICLE_LOSS_HINGE && loss != CHICLE_LOSS_SQUARED) || n_total <= 0 ||
+    if ((loss != CHICLE_LOSS_HINGE && loss != CHICLE_LOSS_SQUARED && loss != CHICLE_LOSS_LOGISTIC) || n_total <= 0 ||
         n_total > INT32_MAX || d <= 0 || !(lambda > 0.0) || n_chunks <= 0 || max_solvers <= 0 ||
         total_entries < 0 || !device_arena || ((uintptr_t)device_arena % ALIGN) != 0)
         return CHICLE_EINVAL;
@@ -586,11 +591,11 @@ static int check_state_arrays(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, c
     if (!y) return fail(c, CHICLE_EINVAL, "chunk %d: y is NULL", chunk_id);
     for (int32_t r = 0; r < n_rows; ++r) {
         if (!std::isfinite(y[r])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: label not finite", chunk_id, r);
-        if (c->loss == CHICLE_LOSS_HINGE && y[r] != 1.0f && y[r] != -1.0f)
+        if (c->loss != CHICLE_LOSS_SQUARED && y[r] != 1.0f && y[r] != -1.0f)
             return fail(c, CHICLE_EINVAL, "chunk %d row %d: hinge label must be +1 or -1", chunk_id, r);
         if (alpha0) {
             if (!std::isfinite(alpha0[r])) return fail(c, CHICLE_EINVAL, "chunk %d row %d: alpha not finite", chunk_id, r);
-            if (c->loss == CHICLE_LOSS_HINGE && (alpha0[r] < 0.0f || alpha0[r] > 1.0f))
+            if (c->loss != CHICLE_LOSS_SQUARED && (alpha0[r] < 0.0f || alpha0[r] > 1.0f))
                 return fail(c, CHICLE_EINVAL, "chunk %d row %d: hinge alpha outside [0,1]", chunk_id, r);
         }
     }
@@ -607,7 +612,7 @@ static int finish_load(chicle_ctx *c, int32_t chunk_id, ChunkDev &ch, const floa
     std::vector<RowState> st(ch.n_rows);
     for (int32_t r = 0; r < ch.n_rows; ++r) {
         st[r].y = y[r]; st[r].alpha = alpha0 ? alpha0[r] : 0.f; st[r].q = q[r];
-        st[r].rw = c->loss == CHICLE_LOSS_HINGE ? 1.f : y[r];   // residual at w = 0
+        st[r].rw = c->loss == CHICLE_LOSS_HINGE ? 1.f : c->loss == CHICLE_LOSS_SQUARED ? y[r] : 0.f;   // residual at w = 0
     }
     HIP_TRY(c, hipMemcpyAsync(sd, st.data(), nb, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));   // host arrays are the caller's again on return
@@ -847,7 +852,9 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
                                               : launch_batched<1>(c, perm_device, perm_next_device);
         } else {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
-            rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device) : launch_rowwise<1>(c, perm_device);
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device)
+                 : c->loss == CHICLE_LOSS_SQUARED ? launch_rowwise<1>(c, perm_device)
+                                                  : launch_rowwise<2>(c, perm_device);
             seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
         }
     }
@@ -972,7 +979,7 @@ int chicle_set_alpha(chicle_ctx *c, int32_t chunk_id, const float *alpha_in)
     const ChunkDev &ch = c->chunks[chunk_id];
     for (int32_t r = 0; r < ch.n_rows; ++r) {
         if (!std::isfinite(alpha_in[r])) return fail(c, CHICLE_EINVAL, "alpha not finite at row %d", r);
-        if (c->loss == CHICLE_LOSS_HINGE && (alpha_in[r] < 0.f || alpha_in[r] > 1.f))
+        if (c->loss != CHICLE_LOSS_SQUARED && (alpha_in[r] < 0.f || alpha_in[r] > 1.f))
             return fail(c, CHICLE_EINVAL, "hinge alpha outside [0,1] at row %d", r);
     }
     HIP_TRY(c, hipMemcpy2DAsync(&ch.st->alpha, sizeof(RowState), alpha_in, sizeof(float), sizeof(float),

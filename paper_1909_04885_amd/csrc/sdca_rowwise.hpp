@@ -28,6 +28,33 @@ __device__ __forceinline__ float dual_step(float a, float y, float rw, float xu,
         an = fminf(fmaxf(an, 0.0f), 1.0f);
         return an - a;
     }
+    if (LOSS == 2) {
+        // Logistic loss: a' = 1 / (1 + exp(-s)) with s the root of f(s) = m - s - r (a'(s) - a), where
+        // m = -y z (rw holds -y x.w) and r = q / c.  f decreases strictly (slope in [-1 - r/4, -1]) and,
+        // a' lying in (0, 1), its root lies in [m - r (1 - a), m + r a].  Newton steps inside that bracket;
+        // a bisection step whenever Newton would leave it or fails to halve the last step (r can be in the
+        // hundreds, where plain Newton cycles between the two flat ends of the sigmoid).
+        const float m = rw - y * xu, r = q / c;
+        float lo = m - r * (1.0f - a), hi = m + r * a;
+        float s = 0.5f * (lo + hi), dx_old = hi - lo, dx = dx_old, ap, f, df;
+        auto eval = [&]() {
+            const float e = __expf(-fabsf(s));
+            ap = s >= 0.f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+            f = (m - s) - r * (ap - a);
+            df = -(1.0f + r * ap * (1.0f - ap));
+        };
+        eval();
+        for (int it = 0; it < 48; ++it) {
+            const bool leaves = ((s - hi) * df - f) * ((s - lo) * df - f) > 0.f;
+            dx_old = dx;
+            if (leaves || fabsf(2.0f * f) > fabsf(dx_old * df)) { dx = 0.5f * (hi - lo); s = lo + dx; }
+            else { dx = f / df; s -= dx; }
+            eval();
+            if (f > 0.f) lo = s; else hi = s;
+            if (fabsf(dx) <= 1e-7f * (1.0f + fabsf(s))) break;     // the step is below fp32 resolution of s
+        }
+        return ap - a;
+    }
     return (rw - xu - a) / (1.0f + q / c);
 }
 
@@ -169,7 +196,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
                 const float xu = block_sum<BLOCK>(part, red);
                 const float delta = dual_step<LOSS>(m.alpha, m.y, m.rw, xu, m.q, sc.c);
                 if (tid == 0) gst(&m.st->alpha, m.alpha + delta);
-                const float coef = delta * (LOSS == 0 ? m.y : 1.0f) * sc.inv_c;
+                const float coef = delta * (LOSS == 1 ? 1.0f : m.y) * sc.inv_c;
                 if (coef != 0.0f) {
 #pragma unroll
                     for (int e = 0; e < EPT; ++e)
@@ -235,7 +262,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
         const float xu = block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, rw, xu, q, sc.c);
         if (tid == 0) ch.st[r].alpha = a + delta;
-        const float coef = delta * (LOSS == 0 ? y : 1.0f) * sc.inv_c;
+        const float coef = delta * (LOSS == 1 ? 1.0f : y) * sc.inv_c;
         if (coef != 0.0f)
             for (int p = tid; p < d; p += BLOCK) v[p] += coef * x[p];
         __syncthreads();

@@ -85,6 +85,9 @@ def test_arena_bytes_and_create_argument_checks(lib):
     assert lib.chicle_create(ctypes.byref(h), 7, 10, 4, 0.1, 1, 1, 0, 10, ctypes.c_void_p(256), 1 << 20, None) == -1
     assert lib.chicle_create(ctypes.byref(h), 0, 10, 4, 0.0, 1, 1, 0, 10, ctypes.c_void_p(256), 1 << 20, None) == -1
     assert lib.chicle_create(ctypes.byref(h), 0, 10, 4, 0.1, 1, 1, 0, 10, ctypes.c_void_p(256), 16, None) == -2
+    # the logistic loss is a valid loss id: with too small an arena it gets as far as the size check
+    assert lib.chicle_create(ctypes.byref(h), 2, 10, 4, 0.1, 1, 1, 0, 10, ctypes.c_void_p(256), 16, None) == -2
+    assert lib.chicle_create(ctypes.byref(h), 3, 10, 4, 0.1, 1, 1, 0, 10, ctypes.c_void_p(256), 16, None) == -1
     assert h.value is None
     assert lib.chicle_last_error(None) == b"null context"
     for fn in ("chicle_aggregate", "chicle_sync"):
