@@ -19,6 +19,7 @@
 #include "layout.hpp"
 #include "policies.hpp"
 #include "sdca_batched.hpp"
+#include "sdca_batched_dense.hpp"
 #include "sdca_rowwise.hpp"
 
 using namespace chicle;
@@ -243,6 +244,27 @@ bool batched_eligible(const chicle_ctx *c)
     // (the blocked recurrence needs the step in closed form: hinge and squared loss)
     return c->loss != CHICLE_LOSS_LOGISTIC && !c->dense && c->max_row_len <= GRAM_MAX_ROW &&
            c->max_list <= BATCHED_MAX_LIST;
+}
+
+// Dense rows too wide to be stored with column ids, narrow enough for a block of 64 to sit in LDS.
+bool dense_blocked_eligible(const chicle_ctx *c)
+{
+    return c->dense && c->loss != CHICLE_LOSS_LOGISTIC && c->d <= DB_MAX_D;
+}
+
+template <int LOSS>
+int launch_dense_blocked(chicle_ctx *c, const int32_t *perm)
+{
+    const RoundScalars sc = scalars(c);
+    const int ml = std::max(c->max_list, 1);
+    const size_t sh = sizeof(float) * db_lds_floats((int)c->d) + 2 * sizeof(int) * (size_t)ml;
+    auto kern = sdca_batched_dense<LOSS>;
+    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+    hipLaunchKernelGGL(kern, dim3(c->K), dim3(DB_THREADS), sh, c->stream, c->chunks_dev, c->solvers_dev,
+                       c->solver_chunks_dev, c->solver_prefix_dev, perm, c->u, c->ld_v, (int)c->d, ml, sc,
+                       c->err_dev);
+    HIP_TRY(c, hipGetLastError());
+    return CHICLE_OK;
 }
 
 template <int LOSS>
@@ -835,13 +857,15 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
     if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
-    bool batched = false;
+    bool batched = false, dense_blocked = false;
     if (c->solver_kind == CHICLE_SOLVER_BATCHED) {
-        if (!batched_eligible(c))
-            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver", GRAM_MAX_ROW, BATCHED_MAX_LIST);
-        batched = true;
+        dense_blocked = dense_blocked_eligible(c);
+        if (!dense_blocked && !batched_eligible(c))
+            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver, or dense rows of at most %d columns, and a loss with a closed-form step", GRAM_MAX_ROW, BATCHED_MAX_LIST, DB_MAX_D);
+        batched = !dense_blocked;
     } else if (c->solver_kind == CHICLE_SOLVER_AUTO) {
         batched = batched_eligible(c);
+        dense_blocked = !batched && dense_blocked_eligible(c);
     }
     seg_begin(c, CHICLE_SEG_LOCAL_EPOCH);
     int rc = CHICLE_OK;
@@ -850,6 +874,11 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
         if (batched) {
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device, perm_next_device)
                                               : launch_batched<1>(c, perm_device, perm_next_device);
+        } else if (dense_blocked) {
+            seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_dense_blocked<0>(c, perm_device)
+                                              : launch_dense_blocked<1>(c, perm_device);
+            seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
         } else {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_rowwise<0>(c, perm_device)
