@@ -68,7 +68,9 @@ enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1, CHICLE_LOSS_L
 enum chicle_solver_kind {
     CHICLE_SOLVER_AUTO = 0,       /* choose from the data shape */
     CHICLE_SOLVER_ROWWISE = 1,    /* one coordinate step at a time */
-    CHICLE_SOLVER_BATCHED = 2     /* blocks of rows via their Gram matrix, same sequence of steps */
+    CHICLE_SOLVER_BATCHED = 2     /* blocks of 64 rows via their Gram matrix, same sequence of steps: sparse rows
+                                     of at most 48 entries (dense rows that short are stored that way), or dense
+                                     rows of at most 320 columns; hinge and squared loss; else EINVAL at the pass */
 };
 
 /* Timed segments reported by chicle_last_kernel_ms. */
