@@ -155,3 +155,20 @@ def test_scale_in_schedule_run_matches_oracle(mods):
     print("gaps", ["%.4f" % x for x in res["gaps"]], flush=True)
     for a, b in zip(res["gaps"], ref):
         assert abs(a - b) <= 1e-3 * abs(b)
+
+
+@pytest.mark.parametrize("K", [1, 17])
+def test_odd_solver_counts_with_the_batched_solver(mods, K):
+    """Solver counts that are not a multiple of the number of L2 partitions (the batched solver pairs every
+    solver with a warming workgroup by index), including a single solver that owns every chunk."""
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "mini")
+    print("\ncase sparse_zipf mini, K =", K, flush=True)
+    table = (np.arange(p.n_chunks) % K).astype(np.int32)
+
+    def tables(r, K_prev, t_prev):
+        return (K, table, table.copy()) if r == 0 else None
+
+    rec = run_lockstep(cfg, p, oracle_mod, binding, rounds=3, solver="batched", ahead=True, tables=tables,
+                       max_solvers=K, log=lambda m: print(m, flush=True))
+    assert [x["K"] for x in rec] == [K] * 3
