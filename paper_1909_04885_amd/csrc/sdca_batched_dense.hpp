@@ -24,8 +24,11 @@ constexpr int DB_G_LD = BATCH + 1;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Dynamic LDS, in floats: X[64][ldx] | Gp[2][64][65] | T[64][65] | u[ldx] | per-row arrays (8 x 64) |
-// then max_list chunk ids and max_list local-row prefixes (ints).  ldx = d rounded up to even, plus 1.
-__host__ __device__ inline int db_ldx(int d) { return ((d + 1) & ~1) + 1; }
+// then max_list chunk ids and max_list local-row prefixes (ints).  Rows are padded with zeros to a multiple
+// of 16 columns (the Gram loop takes 8 columns per half and step); ldx = that + 4 keeps rows 16-byte
+// aligned and spreads them over the banks.
+__host__ __device__ inline int db_dpad(int d) { return (d + 15) & ~15; }
+__host__ __device__ inline int db_ldx(int d) { return db_dpad(d) + 4; }
 __host__ __device__ inline size_t db_lds_floats(int d)
 {
     return (size_t)BATCH * db_ldx(d) + 3 * (size_t)BATCH * DB_G_LD + db_ldx(d) + 8 * BATCH;
@@ -39,7 +42,7 @@ __global__ __launch_bounds__(DB_THREADS) void sdca_batched_dense(
     int *err)
 {
     extern __shared__ __align__(16) float db_smem[];
-    const int ldx = db_ldx(d), d2 = (d + 1) & ~1;
+    const int ldx = db_ldx(d), d2 = db_dpad(d);
     float *X = db_smem;                                  // [64][ldx], columns d .. d2-1 zero
     float *Gp = X + BATCH * ldx;                         // [2][64][65] partial Gram matrices
     float *T = Gp + 2 * BATCH * DB_G_LD;                 // [j][i], zero for j >= i
@@ -95,17 +98,27 @@ __global__ __launch_bounds__(DB_THREADS) void sdca_batched_dense(
             X[row * ldx + k] = (xp != nullptr && k < d) ? xp[k] : 0.f;
         }
         __syncthreads();
-        // 3. G = X X^T on the matrix cores: wavefront -> (tile row, tile column, half of the columns);
-        //    lane l feeds A[l % 32][l / 32] and B[l / 32][l % 32] of a 32 x 2 by 2 x 32 product
+        // 3. G = X X^T on the matrix cores: wavefront -> (tile row, tile column, half of the columns).
+        //    A 32 x 2 by 2 x 32 product takes A[l % 32][l / 32] and B[l / 32][l % 32] from lane l.  Any
+        //    pairing of the columns works for a dot product: per 8 columns a lane reads 4 consecutive ones
+        //    (the lower four for lanes 0..31, the upper four for the others) with one 16-byte LDS read per
+        //    operand and feeds them to 4 products.
         {
             const int ti = wv & 1, tj = (wv >> 1) & 1, kh = wv >> 2;
-            const float *pa = X + (32 * ti + (lane & 31)) * ldx + (lane >> 5);
-            const float *pb = X + (32 * tj + (lane & 31)) * ldx + (lane >> 5);
+            const float *pa = X + (32 * ti + (lane & 31)) * ldx + 4 * (lane >> 5);
+            const float *pb = X + (32 * tj + (lane & 31)) * ldx + 4 * (lane >> 5);
             floatx16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            const int k0 = kh * (d2 / 2) & ~1, k1 = kh == 0 ? ((d2 / 2) & ~1) : d2;
-            for (int k = k0; k < k1; k += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], pb[k], acc, 0, 0, 0);
+            const int k0 = kh * (d2 / 2), k1 = k0 + d2 / 2;          // d2 / 2 is a multiple of 8
+            for (int k = k0; k < k1; k += 8) {
+                const float4 a = *reinterpret_cast<const float4 *>(pa + k);
+                const float4 bq = *reinterpret_cast<const float4 *>(pb + k);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bq.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bq.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bq.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bq.w, acc, 0, 0, 0);
+            }
             // result layout: register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
             float *g = Gp + kh * BATCH * DB_G_LD;
 #pragma unroll
