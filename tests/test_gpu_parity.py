@@ -169,6 +169,38 @@ def test_tiny_ragged_with_empty_row_and_idle_solver(mods, loss, dense):
     g.close()
 
 
+@pytest.mark.parametrize("loss", ["hinge", "squared", "logistic"])
+@pytest.mark.parametrize("d,dense,density", [(48, True, 1.0), (49, True, 1.0), (320, True, 1.0), (321, True, 1.0),
+                                             (200, False, 0.2), (200, False, 0.3), (30, False, 0.9)])
+def test_shapes_on_both_sides_of_every_solver_choice(mods, loss, d, dense, density):
+    """Row widths at the borders between the solvers the library chooses from (dense rows stored with
+    column ids up to 48 columns, the dense blocked solver up to 320, the sparse batched solver up to 48
+    entries per row), each against the oracle for a few rounds with ragged chunks."""
+    oracle_mod, binding = mods
+    from workloads.generate import Problem
+    g = np.random.default_rng(d + 7 * dense)
+    n, chunk, K = 333, 70, 3
+    X = g.standard_normal((n, d)).astype(np.float32)
+    if density < 1.0:
+        X[g.random(X.shape) >= density] = 0
+    X[5] = 0
+    y = g.standard_normal(n).astype(np.float32) if loss == "squared" else np.where(g.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    bounds = np.array(list(range(0, n, chunk)) + [n], dtype=np.int64)
+    if dense:
+        p = Problem("shape", loss, n, d, 0.02, y, bounds, X=X)
+    else:
+        mask = X != 0
+        rp = np.zeros(n + 1, dtype=np.int64)
+        np.cumsum(mask.sum(1), out=rp[1:])
+        p = Problem("shape", loss, n, d, 0.02, y, bounds, row_ptr=rp, col=np.nonzero(mask)[1].astype(np.int32), val=X[mask])
+    print("\ncase shape d=%d dense=%s density=%.1f %s max row %d" %
+          (d, dense, density, loss, int((X != 0).sum(1).max())), flush=True)
+    cfg = {"seed": 3, "rounds": 4, "schedule": [(0, K)], "K": K}
+    table = (np.arange(p.n_chunks) % K).astype(np.int32)
+    run_lockstep(cfg, p, oracle_mod, binding, rounds=4, check_alpha_every=1, log=_log,
+                 tables=lambda r, Kp, tp: (K, table, table.copy()) if r == 0 else None, max_solvers=K)
+
+
 def test_ownership_contract_and_errors(mods):
     oracle_mod, binding = mods
     p = _tiny(binding)
