@@ -241,9 +241,7 @@ bool dense_as_csr(int32_t d) { return d <= GRAM_MAX_ROW; }
 
 bool batched_eligible(const chicle_ctx *c)
 {
-    // (the blocked recurrence needs the step in closed form: hinge and squared loss)
-    return c->loss != CHICLE_LOSS_LOGISTIC && !c->dense && c->max_row_len <= GRAM_MAX_ROW &&
-           c->max_list <= BATCHED_MAX_LIST;
+    return !c->dense && c->max_row_len <= GRAM_MAX_ROW && c->max_list <= BATCHED_MAX_LIST;
 }
 
 // Dense rows too wide to be stored with column ids, narrow enough for a block of 64 to sit in LDS.
@@ -861,7 +859,7 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     if (c->solver_kind == CHICLE_SOLVER_BATCHED) {
         dense_blocked = dense_blocked_eligible(c);
         if (!dense_blocked && !batched_eligible(c))
-            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver, or dense rows of at most %d columns, and a loss with a closed-form step", GRAM_MAX_ROW, BATCHED_MAX_LIST, DB_MAX_D);
+            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver, or dense rows of at most %d columns with the hinge or squared loss", GRAM_MAX_ROW, BATCHED_MAX_LIST, DB_MAX_D);
         batched = !dense_blocked;
     } else if (c->solver_kind == CHICLE_SOLVER_AUTO) {
         batched = batched_eligible(c);
@@ -873,7 +871,8 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     if (rc == CHICLE_OK) {
         if (batched) {
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device, perm_next_device)
-                                              : launch_batched<1>(c, perm_device, perm_next_device);
+                 : c->loss == CHICLE_LOSS_SQUARED ? launch_batched<1>(c, perm_device, perm_next_device)
+                                                  : launch_batched<2>(c, perm_device, perm_next_device);
         } else if (dense_blocked) {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_dense_blocked<0>(c, perm_device)
@@ -1120,7 +1119,8 @@ int chicle_debug_gram(chicle_ctx *c, const int32_t *perm_device, float *tiles_ou
     int rc = drop_ahead(c);
     if (rc) return rc;
     rc = c->loss == CHICLE_LOSS_HINGE ? launch_gram<0>(c, perm_device, c->tile_buf, c->stream)
-                                      : launch_gram<1>(c, perm_device, c->tile_buf, c->stream);
+         : c->loss == CHICLE_LOSS_SQUARED ? launch_gram<1>(c, perm_device, c->tile_buf, c->stream)
+                                          : launch_gram<2>(c, perm_device, c->tile_buf, c->stream);
     if (rc) return rc;
     if (tiles_out) {
         const int64_t want = (int64_t)c->n_tiles * TILE_FLOATS;

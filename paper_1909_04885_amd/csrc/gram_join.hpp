@@ -128,8 +128,8 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
             const float q = L.st.z;
             if (q != 0.f && n > 0 && n <= GRAM_MAX_ROW) {
                 len = n; cp = L.colp + L.rp.x; vp = L.valp + L.rp.x;
-                sgn = LOSS == 0 ? L.st.x : 1.f;
-                scale = LOSS == 0 ? -1.f / q : -1.f / (c + q);
+                sgn = LOSS == 1 ? 1.f : L.st.x;
+                scale = LOSS == 0 ? -1.f / q : LOSS == 1 ? -1.f / (c + q) : -1.f / c;
             }
         }
         if (len == 0) { cp = dummy_col; vp = dummy_val; }

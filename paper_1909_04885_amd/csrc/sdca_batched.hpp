@@ -8,7 +8,8 @@
 // squared: t = delta = c/(c+q) (y - alpha - z)) the recurrence becomes
 //     delta_j = clamp_j(t_j);   t_i += delta_j T_ij,
 //     T_ij = -y_i y_j G_ij / q_i (hinge),   T_ij = -G_ij / (c + q_i) (squared),
-// three dependent instructions per step in one wavefront (lane i owns t_i).  The dot products with
+// three dependent instructions per step in one wavefront (lane i owns t_i).  The logistic loss keeps
+// m_i = -y_i z_i in place of t_i and solves each step's scalar equation inside the recurrence.  The dot products with
 // the private vector (gather), the alpha updates and the scatter into the private vector are done a
 // block at a time by the other wavefronts of the workgroup, off the critical path; the matrices T
 // depend on the data and the visiting order only and are produced beforehand by a separate kernel
@@ -92,6 +93,32 @@ __device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, 
         x = fmaf(s, sh.Tx[buf][j][lane], x);
     }
     sh.delta[buf][lane] = clamp_step<LOSS>(t, lo, hi);
+    x_carry = x;
+}
+
+// The same for the logistic loss, whose step has no closed form.  Lane i owns m_i = -y_i z_i; step j is
+// solved for the whole wavefront from lane j's values (a uniform computation), then
+//     m_i += delta_j T_ij,   T_ij = -y_i y_j G_ij / c.
+// Slots: t0 = m at the start of the block, lo = alpha, hi = r = q / c (0 marks a row to skip).
+template <>
+__device__ __forceinline__ void chain_block<2>(BatchedShared &sh, int i, int lane, float &x_carry)
+{
+    const int ring = i & (RING - 1), buf = i & 1;
+    float m = sh.t0[ring][lane] + x_carry;
+    const float a = sh.lo[ring][lane], r = sh.hi[ring][lane];
+    float x = 0.f, mine = 0.f;
+#pragma unroll 2
+    for (int j = 0; j < BATCH; ++j) {
+        const float mj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), j));
+        const float aj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j));
+        const float rj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), j));
+        float d = 0.f;
+        if (rj > 0.f) d = logistic_step(mj, rj, aj, mj + rj * (aj - 0.5f));
+        m = fmaf(d, sh.Tw[buf][j][lane], m);
+        x = fmaf(d, sh.Tx[buf][j][lane], x);
+        mine = lane == j ? d : mine;
+    }
+    sh.delta[buf][lane] = mine;
     x_carry = x;
 }
 
@@ -283,7 +310,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                 const RowSlot &r = sh.rows[(i - 1) & (RING - 1)][rho];
                 const float dl = sh.delta[(i - 1) & 1][rho];
                 if (r.len > 0 && dl != 0.f) {
-                    const float coef = dl * (LOSS == 0 ? r.y : 1.f) * sc.inv_c;
+                    const float coef = dl * (LOSS == 1 ? 1.f : r.y) * sc.inv_c;
 #pragma unroll
                     for (int e = 0; e < ENT; ++e)
                         if (s_v[e] != 0.f) {
@@ -292,7 +319,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                         }
                     if (sub == 0) {
                         float an = r.alpha + dl;
-                        if (LOSS == 0) an = fminf(fmaxf(an, 0.f), 1.f);
+                        if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
                         gst(&r.st->alpha, an);
                     }
                 }
@@ -330,8 +357,11 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                         if (LOSS == 0) {
                             t0 = (sc.c / r.q) * (r.rw - r.y * part);
                             lo = -r.alpha; hi = 1.f - r.alpha;
-                        } else {
+                        } else if (LOSS == 1) {
                             t0 = (sc.c / (sc.c + r.q)) * (r.rw - r.alpha - part);
+                        } else {
+                            t0 = r.rw - r.y * part;
+                            lo = r.alpha; hi = r.q * sc.inv_c;
                         }
                     }
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;

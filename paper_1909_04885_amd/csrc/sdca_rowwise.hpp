@@ -19,7 +19,35 @@
 
 namespace chicle {
 
-// rw: residual at w (see above); xu = x_i . u_k.
+// Logistic loss, one dual step: a' = 1 / (1 + exp(-s)) with s the root of f(s) = m - s - r (a'(s) - a),
+// where m = -y z and r = q / c; returns a' - a.  f decreases strictly (slope in [-1 - r/4, -1]) and, a'
+// lying in (0, 1), its root lies in [m - r (1 - a), m + r a].  Newton steps from s0 inside that bracket; a
+// bisection step whenever Newton would leave it or fails to halve the last step (r can be in the
+// hundreds, where plain Newton cycles between the two flat ends of the sigmoid).
+__device__ __forceinline__ float logistic_step(float m, float r, float a, float s0)
+{
+    float lo = m - r * (1.0f - a), hi = m + r * a;
+    float s = fminf(fmaxf(s0, lo), hi), dx_old = hi - lo, dx = dx_old, ap, f, df;
+    auto eval = [&]() {
+        const float e = __expf(-fabsf(s));
+        ap = s >= 0.f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+        f = (m - s) - r * (ap - a);
+        df = -(1.0f + r * ap * (1.0f - ap));
+    };
+    eval();
+    for (int it = 0; it < 48; ++it) {
+        const bool leaves = ((s - hi) * df - f) * ((s - lo) * df - f) > 0.f;
+        dx_old = dx;
+        if (leaves || fabsf(2.0f * f) > fabsf(dx_old * df)) { dx = 0.5f * (hi - lo); s = lo + dx; }
+        else { dx = f / df; s -= dx; }
+        eval();
+        if (f > 0.f) lo = s; else hi = s;
+        if (fabsf(dx) <= 1e-7f * (1.0f + fabsf(s))) break;     // the step is below fp32 resolution of s
+    }
+    return ap - a;
+}
+
+// rw: residual at w (see above; logistic: -y x_i.w); xu = x_i . u_k.
 template <int LOSS>
 __device__ __forceinline__ float dual_step(float a, float y, float rw, float xu, float q, float c)
 {
@@ -29,31 +57,8 @@ __device__ __forceinline__ float dual_step(float a, float y, float rw, float xu,
         return an - a;
     }
     if (LOSS == 2) {
-        // Logistic loss: a' = 1 / (1 + exp(-s)) with s the root of f(s) = m - s - r (a'(s) - a), where
-        // m = -y z (rw holds -y x.w) and r = q / c.  f decreases strictly (slope in [-1 - r/4, -1]) and,
-        // a' lying in (0, 1), its root lies in [m - r (1 - a), m + r a].  Newton steps inside that bracket;
-        // a bisection step whenever Newton would leave it or fails to halve the last step (r can be in the
-        // hundreds, where plain Newton cycles between the two flat ends of the sigmoid).
         const float m = rw - y * xu, r = q / c;
-        float lo = m - r * (1.0f - a), hi = m + r * a;
-        float s = 0.5f * (lo + hi), dx_old = hi - lo, dx = dx_old, ap, f, df;
-        auto eval = [&]() {
-            const float e = __expf(-fabsf(s));
-            ap = s >= 0.f ? 1.0f / (1.0f + e) : e / (1.0f + e);
-            f = (m - s) - r * (ap - a);
-            df = -(1.0f + r * ap * (1.0f - ap));
-        };
-        eval();
-        for (int it = 0; it < 48; ++it) {
-            const bool leaves = ((s - hi) * df - f) * ((s - lo) * df - f) > 0.f;
-            dx_old = dx;
-            if (leaves || fabsf(2.0f * f) > fabsf(dx_old * df)) { dx = 0.5f * (hi - lo); s = lo + dx; }
-            else { dx = f / df; s -= dx; }
-            eval();
-            if (f > 0.f) lo = s; else hi = s;
-            if (fabsf(dx) <= 1e-7f * (1.0f + fabsf(s))) break;     // the step is below fp32 resolution of s
-        }
-        return ap - a;
+        return logistic_step(m, r, a, m + r * (a - 0.5f));
     }
     return (rw - xu - a) / (1.0f + q / c);
 }

@@ -41,21 +41,36 @@ def test_mini_all_solvers_every_round(mods, name, solver, ahead):
     run_lockstep(cfg, p, oracle_mod, binding, solver=solver, check_alpha_every=1, log=_log, ahead=ahead)
 
 
-@pytest.mark.parametrize("name,size", [("dense_hinge", "mini"), ("sparse_zipf", "mini"), ("sparse_longrow", "mini"),
-                                       ("elastic", "mini"), ("dense_hinge", "full")])
-def test_logistic_loss_every_round(mods, name, size):
-    """The same data and schedules with the logistic loss (labels are +-1 already): the row-wise solver's
-    safeguarded Newton step in fp32 against the oracle's bisection in fp64."""
+@pytest.mark.parametrize("name,size,solver,ahead", [
+    ("dense_hinge", "mini", "auto", False), ("sparse_zipf", "mini", "rowwise", False),
+    ("sparse_zipf", "mini", "batched", False), ("sparse_longrow", "mini", "auto", False),
+    ("elastic", "mini", "rowwise", False), ("elastic", "mini", "batched", True),
+    ("dense_hinge", "full", "auto", False)])
+def test_logistic_loss_every_round(mods, name, size, solver, ahead):
+    """The same data and schedules with the logistic loss (labels are +-1 already): the library's
+    safeguarded Newton step in fp32, in the row-wise solver and inside the blocked recurrence, against
+    the oracle's bisection in fp64."""
     import dataclasses
     oracle_mod, binding = mods
     cfg, p = cached_problem(name, size)
     p = dataclasses.replace(p, loss="logistic")
-    print("\ncase", name, size, "logistic n=%d d=%d" % (p.n, p.d), flush=True)
+    print("\ncase", name, size, solver, "logistic n=%d d=%d" % (p.n, p.d), flush=True)
     # The full dense case converges within a few rounds (gap 1e-6 of its start after 6); from there the
     # step a' - a cancels in fp32 and the error relative to a vanishing Delta w passes 1e-4, so it stops there.
     rounds = 6 if size == "full" else None
-    rec = run_lockstep(cfg, p, oracle_mod, binding, rounds=rounds, check_alpha_every=1, log=_log)
+    rec = run_lockstep(cfg, p, oracle_mod, binding, rounds=rounds, solver=solver, check_alpha_every=1, log=_log,
+                       ahead=ahead)
     assert abs(rec[0]["P_ref"] - rec[0]["P_gpu"]) < 1e-5 and rec[-1]["gap_ref"] < np.log(2.0)
+
+
+def test_logistic_full_sparse_zipf(mods):
+    """The benchmark's sizes with the logistic loss (blocked solver, tiles of the next pass prepared ahead)."""
+    import dataclasses
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "full")
+    p = dataclasses.replace(p, loss="logistic")
+    print("\ncase sparse_zipf full logistic n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, rounds=5, sample_solvers=[0, 13, 31], log=_log, ahead=True)
 
 
 @pytest.mark.parametrize("name", ["dense_hinge", "dense_ridge"])
