@@ -79,7 +79,7 @@ struct BatchedShared {
 
 // The chain: 64 sequential steps of one block.  Lane i owns row i.
 template <int LOSS>
-__device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, float &x_carry)
+__device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, float &x_carry, float inv_c)
 {
     const int ring = i & (RING - 1), buf = i & 1;
     float t = sh.t0[ring][lane] + x_carry;
@@ -96,24 +96,66 @@ __device__ __forceinline__ void chain_block(BatchedShared &sh, int i, int lane, 
     x_carry = x;
 }
 
+// One dual step of the logistic loss computed by a whole wavefront from uniform arguments (see
+// logistic_step for the equation).  f decreases strictly, so the 64 lanes evaluate it at 64 evenly spaced
+// points of the bracket and the first lane with f <= 0 narrows the bracket 63-fold; when the bracket is so
+// narrow that a chord of f misses the root by less than fp32 resolution (|f''| <= 0.0963 r, |f'| >= 1:
+// error <= 0.012 h^2 r), the root and a' are read off the chord.  [lo, lo + w] is a bracket of the root:
+// the general one, [m - r (1 - a), m + r a], costs two evaluations for r of order one and four for r in
+// the hundreds; no derivative, no iteration that could cycle.
+__device__ __forceinline__ float logistic_step_wave(float m, float r, float a, float lo, float w, int lane)
+{
+    const float frac = (float)lane * (1.0f / 63.0f);
+    float s = 0.f, ap = 0.f, f = 0.f;
+    int k = 1;
+    for (int it = 0; it < 8; ++it) {
+        s = fmaf(frac, w, lo);
+        const float e = __expf(-fabsf(s));
+        const float t = __builtin_amdgcn_rcpf(1.0f + e);
+        ap = s >= 0.f ? t : e * t;
+        f = (m - s) - r * (ap - a);
+        const unsigned long long pos = __ballot(f > 0.f);
+        k = ~pos ? __builtin_ctzll(~pos) : 64;
+        k = min(max(k, 1), 63);
+        const float h = w * (1.0f / 63.0f);
+        if (h * h * r <= 4e-6f || h <= 1e-7f * (1.0f + fabsf(lo))) break;
+        lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), k - 1));
+        w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), k)) - lo;
+    }
+    const float f0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f), k - 1));
+    const float f1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f), k));
+    const float a0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ap), k - 1));
+    const float a1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ap), k));
+    const float den = f0 - f1;
+    const float th = den > 0.f ? fminf(fmaxf(f0 * __builtin_amdgcn_rcpf(den), 0.f), 1.f) : 0.5f;
+    return fmaf(th, a1 - a0, a0) - a;
+}
+
 // The same for the logistic loss, whose step has no closed form.  Lane i owns m_i = -y_i z_i; step j is
-// solved for the whole wavefront from lane j's values (a uniform computation), then
+// solved by the whole wavefront from lane j's values, then
 //     m_i += delta_j T_ij,   T_ij = -y_i y_j G_ij / c.
-// Slots: t0 = m at the start of the block, lo = alpha, hi = r = q / c (0 marks a row to skip).
+// The helpers have solved every row's equation for its m at the start of the block (slot t0; the root in
+// slot lo).  The root moves in the direction of m and by no more (ds/dm = 1 / (1 + r a'(1 - a')) lies in
+// (0, 1]), so by the time of the row's turn it lies between the old root and the old root + (m - t0): a
+// bracket as narrow as the block's own corrections, for which one evaluation is usually enough.
 template <>
-__device__ __forceinline__ void chain_block<2>(BatchedShared &sh, int i, int lane, float &x_carry)
+__device__ __forceinline__ void chain_block<2>(BatchedShared &sh, int i, int lane, float &x_carry, float inv_c)
 {
     const int ring = i & (RING - 1), buf = i & 1;
-    float m = sh.t0[ring][lane] + x_carry;
-    const float a = sh.lo[ring][lane], r = sh.hi[ring][lane];
+    const float m0 = sh.t0[ring][lane], s0 = sh.lo[ring][lane];
+    float m = m0 + x_carry;
+    const RowSlot &row = sh.rows[ring][lane];
+    const float a = row.alpha, r = row.len > 0 ? row.q * inv_c : 0.f;      // r = 0 marks a row to skip
     float x = 0.f, mine = 0.f;
 #pragma unroll 2
     for (int j = 0; j < BATCH; ++j) {
         const float mj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), j));
         const float aj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j));
         const float rj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), j));
+        const float dm = mj - __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m0), j));
+        const float sj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s0), j));
         float d = 0.f;
-        if (rj > 0.f) d = logistic_step(mj, rj, aj, mj + rj * (aj - 0.5f));
+        if (rj > 0.f) d = logistic_step_wave(mj, rj, aj, sj + fminf(dm, 0.f), fabsf(dm), lane);
         m = fmaf(d, sh.Tw[buf][j][lane], m);
         x = fmaf(d, sh.Tx[buf][j][lane], x);
         mine = lane == j ? d : mine;
@@ -233,7 +275,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         if (tid == BATCHED_THREADS - 1 && i > 0)
             __hip_atomic_store(progress + sid, i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (is_chain) {
-            if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry);
+            if (i >= 0 && i < nb) chain_block<LOSS>(sh, i, lane, x_carry, sc.inv_c);
         } else if (is_service) {
             // tiles for iteration i + 1 (wavefront 9: own part of T(i+1), wavefront 10: cross part of
             // T(i+2), 16 KB each) were fetched into registers during the last iteration
@@ -361,7 +403,8 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
                             t0 = (sc.c / (sc.c + r.q)) * (r.rw - r.alpha - part);
                         } else {
                             t0 = r.rw - r.y * part;
-                            lo = r.alpha; hi = r.q * sc.inv_c;
+                            const float rr = r.q * sc.inv_c;
+                            logistic_step(t0, rr, r.alpha, t0 + rr * (r.alpha - 0.5f), &lo);   // lo: the root for t0
                         }
                     }
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;

@@ -23,8 +23,8 @@ namespace chicle {
 // where m = -y z and r = q / c; returns a' - a.  f decreases strictly (slope in [-1 - r/4, -1]) and, a'
 // lying in (0, 1), its root lies in [m - r (1 - a), m + r a].  Newton steps from s0 inside that bracket; a
 // bisection step whenever Newton would leave it or fails to halve the last step (r can be in the
-// hundreds, where plain Newton cycles between the two flat ends of the sigmoid).
-__device__ __forceinline__ float logistic_step(float m, float r, float a, float s0)
+// hundreds, where plain Newton cycles between the two flat ends of the sigmoid).  *root receives s.
+__device__ __forceinline__ float logistic_step(float m, float r, float a, float s0, float *root = nullptr)
 {
     float lo = m - r * (1.0f - a), hi = m + r * a;
     float s = fminf(fmaxf(s0, lo), hi), dx_old = hi - lo, dx = dx_old, ap, f, df;
@@ -44,6 +44,7 @@ __device__ __forceinline__ float logistic_step(float m, float r, float a, float 
         if (f > 0.f) lo = s; else hi = s;
         if (fabsf(dx) <= 1e-7f * (1.0f + fabsf(s))) break;     // the step is below fp32 resolution of s
     }
+    if (root) *root = s;
     return ap - a;
 }
 
