@@ -16,7 +16,7 @@
  *   logistic: loss_i(z) = log(1 + exp(-y_i z)), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]; its coordinate
  *             step has no closed form: the scalar equation is solved numerically (a safeguarded Newton
  *             iteration in the row-wise solver; in the batched solver for sparse rows a wavefront narrows a
- *             bracket 63-fold per evaluation); dense rows wider than 48 columns use the row-wise solver
+ *             bracket 63-fold per evaluation)
  *
  * Data live in HBM as chunks (Section 3 "Uni-tasks", Section 4.4 "In-memory chunk data
  * format"): a chunk is one contiguous block holding a run of rows (CSR or dense) together with
@@ -72,8 +72,7 @@ enum chicle_solver_kind {
     CHICLE_SOLVER_ROWWISE = 1,    /* one coordinate step at a time */
     CHICLE_SOLVER_BATCHED = 2     /* blocks of 64 rows via their Gram matrix, same sequence of steps: sparse rows
                                      of at most 48 entries (dense rows that short are stored that way), or dense
-                                     rows of at most 320 columns with the hinge or squared loss; else EINVAL at
-                                     the pass */
+                                     rows of at most 320 columns; else EINVAL at the pass */
 };
 
 /* Timed segments reported by chicle_last_kernel_ms. */

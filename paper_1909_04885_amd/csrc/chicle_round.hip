@@ -247,7 +247,7 @@ bool batched_eligible(const chicle_ctx *c)
 // Dense rows too wide to be stored with column ids, narrow enough for a block of 64 to sit in LDS.
 bool dense_blocked_eligible(const chicle_ctx *c)
 {
-    return c->dense && c->loss != CHICLE_LOSS_LOGISTIC && c->d <= DB_MAX_D;
+    return c->dense && c->d <= DB_MAX_D;
 }
 
 template <int LOSS>
@@ -859,7 +859,7 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     if (c->solver_kind == CHICLE_SOLVER_BATCHED) {
         dense_blocked = dense_blocked_eligible(c);
         if (!dense_blocked && !batched_eligible(c))
-            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver, or dense rows of at most %d columns with the hinge or squared loss", GRAM_MAX_ROW, BATCHED_MAX_LIST, DB_MAX_D);
+            return fail(c, CHICLE_EINVAL, "batched solver needs sparse rows of at most %d entries and at most %d chunks per solver, or dense rows of at most %d columns", GRAM_MAX_ROW, BATCHED_MAX_LIST, DB_MAX_D);
         batched = !dense_blocked;
     } else if (c->solver_kind == CHICLE_SOLVER_AUTO) {
         batched = batched_eligible(c);
@@ -876,7 +876,8 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
         } else if (dense_blocked) {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_dense_blocked<0>(c, perm_device)
-                                              : launch_dense_blocked<1>(c, perm_device);
+                 : c->loss == CHICLE_LOSS_SQUARED ? launch_dense_blocked<1>(c, perm_device)
+                                                  : launch_dense_blocked<2>(c, perm_device);
             seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
         } else {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);

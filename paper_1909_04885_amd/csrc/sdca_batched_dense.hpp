@@ -5,7 +5,7 @@
 // themselves, so the blocks are taken strictly one after the other (no lookahead, no cross term):
 //   rows of the block -> LDS;  G = X_b X_b^T (a dense contraction: matrix cores, fp32 in / fp32 out);
 //   t0 = unclipped steps against the private vector;  the recurrence of sdca_batched.hpp over the
-//   strictly lower part of G;  u += X_b^T coef;  alpha.
+//   strictly lower part of G (all three losses);  u += X_b^T coef;  alpha.
 // fp32 matrix instructions give twice the multiply-adds per cycle of the vector units here (packed fp32
 // vector operations are not used in this library).
 #pragma once
@@ -138,8 +138,13 @@ __global__ __launch_bounds__(DB_THREADS) void sdca_batched_dense(
                     if (LOSS == 0) {
                         t0 = (sc.c / q) * (r_rw[row] - r_y[row] * part);
                         lo = -r_a[row]; hi = 1.f - r_a[row];
-                    } else {
+                    } else if (LOSS == 1) {
                         t0 = (sc.c / (sc.c + q)) * (r_rw[row] - r_a[row] - part);
+                    } else {
+                        // logistic: t0 = m = -y z, hi = r = q / c, lo = the root of the row's equation for this m
+                        t0 = r_rw[row] - r_y[row] * part;
+                        hi = q * sc.inv_c;
+                        logistic_step(t0, hi, r_a[row], t0 + hi * (r_a[row] - 0.5f), &lo);
                     }
                 }
                 r_t0[row] = t0; r_lo[row] = lo; r_hi[row] = hi;
@@ -153,30 +158,47 @@ __global__ __launch_bounds__(DB_THREADS) void sdca_batched_dense(
             const float q = r_q[i];
             if (j < i && q != 0.f) {
                 const float g = Gp[j * DB_G_LD + i] + Gp[BATCH * DB_G_LD + j * DB_G_LD + i];
-                v = LOSS == 0 ? -r_y[i] * r_y[j] * g / q : -g / (sc.c + q);
+                v = LOSS == 0 ? -r_y[i] * r_y[j] * g / q : LOSS == 1 ? -g / (sc.c + q) : -r_y[i] * r_y[j] * g * sc.inv_c;
             }
             T[j * DB_G_LD + i] = v;
         }
         __syncthreads();
         // 5. the recurrence (one wavefront)
         if (wv == 0) {
-            float t = r_t0[lane];
+            float t = r_t0[lane], dl;
             const float lo = r_lo[lane], hi = r_hi[lane];
+            if (LOSS == 2) {
+                // lane i keeps m_i; step j is solved by the whole wavefront from a bracket between the root
+                // found for the row's m at the start of the block and that root moved by the change of m
+                const float a = r_a[lane];
+                dl = 0.f;
+#pragma unroll 2
+                for (int j = 0; j < BATCH; ++j) {
+                    const float mj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), j));
+                    const float aj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j));
+                    const float rj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(hi), j));
+                    const float dm = mj - r_t0[j];
+                    float dj = 0.f;
+                    if (rj > 0.f) dj = logistic_step_wave(mj, rj, aj, r_lo[j] + fminf(dm, 0.f), fabsf(dm), lane);
+                    t = fmaf(dj, T[j * DB_G_LD + lane], t);
+                    dl = lane == j ? dj : dl;
+                }
+            } else {
 #pragma unroll 8
-            for (int j = 0; j < BATCH; ++j) {
-                const float dl = clamp_step<LOSS>(t, lo, hi);
-                const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dl), j));
-                t = fmaf(s, T[j * DB_G_LD + lane], t);
+                for (int j = 0; j < BATCH; ++j) {
+                    const float dj = clamp_step<LOSS>(t, lo, hi);
+                    const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dj), j));
+                    t = fmaf(s, T[j * DB_G_LD + lane], t);
+                }
+                dl = clamp_step<LOSS>(t, lo, hi);
             }
-            const float dl = clamp_step<LOSS>(t, lo, hi);
-            r_dl[lane] = dl;
             if (r_st[lane] != nullptr) {
                 float an = r_a[lane] + dl;
-                if (LOSS == 0) an = fminf(fmaxf(an, 0.f), 1.f);
+                if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
                 gst(&r_st[lane]->alpha, an);
             }
             // coefficient of the row in the update of the private vector, in place of its delta
-            r_dl[lane] = dl * (LOSS == 0 ? r_y[lane] : 1.f) * sc.inv_c;
+            r_dl[lane] = dl * (LOSS == 1 ? 1.f : r_y[lane]) * sc.inv_c;
         }
         __syncthreads();
         // 6. u += X^T coef, one column per thread
