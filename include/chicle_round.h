@@ -14,9 +14,8 @@
  *   hinge   : loss_i(z) = max(0, 1 - y_i z), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]
  *   squared : loss_i(z) = (z - y_i)^2 / 2,  s_i = 1,  a_i real
  *   logistic: loss_i(z) = log(1 + exp(-y_i z)), y_i in {-1,+1}, s_i = y_i, a_i in [0,1]; its coordinate
- *             step has no closed form: the scalar equation is solved numerically (a safeguarded Newton
- *             iteration in the row-wise solver; in the batched solver for sparse rows a wavefront narrows a
- *             bracket 63-fold per evaluation)
+ *             step has no closed form: the scalar equation is solved numerically (a wavefront evaluates it at
+ *             64 points of a bracket and narrows the bracket 63-fold per evaluation)
  *
  * Data live in HBM as chunks (Section 3 "Uni-tasks", Section 4.4 "In-memory chunk data
  * format"): a chunk is one contiguous block holding a run of rows (CSR or dense) together with

@@ -48,7 +48,43 @@ __device__ __forceinline__ float logistic_step(float m, float r, float a, float 
     return ap - a;
 }
 
-// rw: residual at w (see above; logistic: -y x_i.w); xu = x_i . u_k.
+// One dual step of the logistic loss computed by a whole wavefront from uniform arguments (see
+// logistic_step for the equation).  f decreases strictly, so the 64 lanes evaluate it at 64 evenly spaced
+// points of the bracket and the first lane with f <= 0 narrows the bracket 63-fold; when the bracket is so
+// narrow that a chord of f misses the root by less than fp32 resolution (|f''| <= 0.0963 r, |f'| >= 1:
+// error <= 0.012 h^2 r), the root and a' are read off the chord.  [lo, lo + w] is a bracket of the root:
+// the general one, [m - r (1 - a), m + r a], costs two evaluations for r of order one and four for r in
+// the hundreds; no derivative, no iteration that could cycle.
+__device__ __forceinline__ float logistic_step_wave(float m, float r, float a, float lo, float w, int lane)
+{
+    const float frac = (float)lane * (1.0f / 63.0f);
+    float s = 0.f, ap = 0.f, f = 0.f;
+    int k = 1;
+    for (int it = 0; it < 8; ++it) {
+        s = fmaf(frac, w, lo);
+        const float e = __expf(-fabsf(s));
+        const float t = __builtin_amdgcn_rcpf(1.0f + e);
+        ap = s >= 0.f ? t : e * t;
+        f = (m - s) - r * (ap - a);
+        const unsigned long long pos = __ballot(f > 0.f);
+        k = ~pos ? __builtin_ctzll(~pos) : 64;
+        k = min(max(k, 1), 63);
+        const float h = w * (1.0f / 63.0f);
+        if (h * h * r <= 4e-6f || h <= 1e-7f * (1.0f + fabsf(lo))) break;
+        lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), k - 1));
+        w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), k)) - lo;
+    }
+    const float f0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f), k - 1));
+    const float f1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f), k));
+    const float a0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ap), k - 1));
+    const float a1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ap), k));
+    const float den = f0 - f1;
+    const float th = den > 0.f ? fminf(fmaxf(f0 * __builtin_amdgcn_rcpf(den), 0.f), 1.f) : 0.5f;
+    return fmaf(th, a1 - a0, a0) - a;
+}
+
+// rw: residual at w (see above; logistic: -y x_i.w); xu = x_i . u_k.  The arguments are the same in every
+// lane of a wavefront (the logistic step is computed by the wavefront as a whole).
 template <int LOSS>
 __device__ __forceinline__ float dual_step(float a, float y, float rw, float xu, float q, float c)
 {
@@ -58,8 +94,11 @@ __device__ __forceinline__ float dual_step(float a, float y, float rw, float xu,
         return an - a;
     }
     if (LOSS == 2) {
-        const float m = rw - y * xu, r = q / c;
-        return logistic_step(m, r, a, m + r * (a - 0.5f));
+        // (taken from the first lane so that the compiler knows them to be uniform)
+        const float m = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(rw - y * xu)));
+        const float r = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(q / c)));
+        const float a1 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a)));
+        return logistic_step_wave(m, r, a1, m - r * (1.0f - a1), r, threadIdx.x & 63);
     }
     return (rw - xu - a) / (1.0f + q / c);
 }

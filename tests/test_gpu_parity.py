@@ -47,9 +47,9 @@ def test_mini_all_solvers_every_round(mods, name, solver, ahead):
     ("elastic", "mini", "rowwise", False), ("elastic", "mini", "batched", True),
     ("dense_hinge", "full", "auto", False)])
 def test_logistic_loss_every_round(mods, name, size, solver, ahead):
-    """The same data and schedules with the logistic loss (labels are +-1 already): the library's
-    safeguarded Newton step in fp32, in the row-wise solver and inside the blocked recurrence, against
-    the oracle's bisection in fp64."""
+    """The same data and schedules with the logistic loss (labels are +-1 already): the library's fp32
+    root search, in the row-wise solvers and inside the blocked recurrences, against the oracle's
+    bisection in fp64."""
     import dataclasses
     oracle_mod, binding = mods
     cfg, p = cached_problem(name, size)
