@@ -165,6 +165,19 @@ int chicle_scale_in(const int32_t *chunk_to_solver, int32_t n_chunks, int32_t K_
 int chicle_rebalance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, const double *unit_time,
                      int32_t n_iterations, int32_t max_moves, int32_t *chunk_to_solver, int32_t *n_moved_out);
 
+/* When to scale in (host, pure).  Section 2.2 cites that starting with many partitions and reducing them
+ * after a few iterations speeds up convergence, and the evaluation's summary that such changes pay once
+ * convergence slows down; the rule itself is this library's: a round has stalled when the gap after it is
+ * more than stall_ratio times the gap before it, and after `patience` stalled rounds in a row the number
+ * of solvers is halved (rounded up, not below K_min).
+ *   gap           the duality gap before the first round and after every round so far (n_gaps entries)
+ *   since_change  rounds run with the current K (only those count towards patience)
+ * Returns the number of solvers for the next round (K when nothing changes), or a negative value for
+ * invalid arguments (null gap, n_gaps < 1, K < 1, K_min < 1, stall_ratio outside (0, 1], patience < 1,
+ * since_change < 0). */
+int32_t chicle_next_solver_count(const double *gap, int32_t n_gaps, int32_t K, int32_t K_min,
+                                 double stall_ratio, int32_t patience, int32_t since_change);
+
 /* Scheduler step between iterations: give every chunk to one of K solvers (host table of n_chunks
  * entries in [0, K)); sigma becomes K; every solver's private vector is re-seeded with w.  A solver
  * may own no chunk.  alpha is not touched.  A solver's local rows are its chunks in ascending chunk id,

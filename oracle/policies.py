@@ -15,6 +15,11 @@ What the prose leaves open is fixed here (and listed among the readings of the p
   * receivers are served in turn, one chunk each, in the order the chunks are handed over;
   * rebalancing moves one chunk at a time from the solver that would finish last to the one that
     would finish first, lightest chunk first, and at most `max_moves` chunks per call.
+
+Section 2.2 cites that starting with many partitions and reducing them after a few iterations speeds
+up convergence, and the summary of the evaluation that such changes pay once convergence slows down.
+The paper gives no rule; the one fixed here: a round stalls when it leaves more than `stall_ratio` of
+the gap it started from, and `patience` stalled rounds in a row under the current K halve K.
 """
 from __future__ import annotations
 
@@ -68,3 +73,14 @@ def rebalance(load: Sequence[int], K: int, unit_time: Sequence[Sequence[float]],
         new[pick] = fast
         moved += 1
     return new, moved
+
+
+def next_solver_count(gaps: Sequence[float], K: int, K_min: int, stall_ratio: float, patience: int,
+                      since_change: int) -> int:
+    """Number of solvers for the next round, from the gap before the first round and after each round."""
+    if K <= K_min or since_change < patience or len(gaps) < patience + 1:
+        return K
+    recent = range(len(gaps) - patience, len(gaps))
+    if all(gaps[t] > stall_ratio * gaps[t - 1] for t in recent):
+        return max(K_min, -(-K // 2))
+    return K

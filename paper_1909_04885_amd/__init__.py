@@ -5,4 +5,4 @@
 used only to allocate device memory and to supply the HIP stream.
 """
 from .binding import (ChicleError, ChicleRound, balance, library_path, load_library,  # noqa: F401
-                      projected_iteration_time, rebalance, scale_in, scale_out)
+                      next_solver_count, projected_iteration_time, rebalance, scale_in, scale_out)

@@ -29,7 +29,7 @@ EXPORTS = [
     "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
     "chicle_solver_ms", "chicle_projected_iteration_time", "chicle_scale_out", "chicle_scale_in",
-    "chicle_rebalance",
+    "chicle_rebalance", "chicle_next_solver_count",
 ]
 
 
@@ -89,6 +89,7 @@ def load_library():
         "chicle_scale_out": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "chicle_scale_in": (ctypes.c_int, [vp, i32, i32, i32, vp]),
         "chicle_rebalance": (ctypes.c_int, [vp, i32, i32, vp, i32, i32, vp, ctypes.POINTER(i32)]),
+        "chicle_next_solver_count": (i32, [vp, i32, i32, i32, ctypes.c_double, i32, i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -170,6 +171,17 @@ def rebalance(chunk_load, K: int, unit_time, table, max_moves: int):
     if rc != OK:
         raise ChicleError(rc, "chicle_rebalance")
     return t, int(moved.value)
+
+
+def next_solver_count(gaps, K: int, K_min: int, stall_ratio: float, patience: int, since_change: int) -> int:
+    """chicle_next_solver_count: the number of solvers for the next round (host only)."""
+    L = load_library()
+    g = _host(gaps, np.float64)
+    rc = L.chicle_next_solver_count(_ptr(g), g.size, int(K), int(K_min), float(stall_ratio), int(patience),
+                                    int(since_change))
+    if rc < 0:
+        raise ChicleError(EINVAL, "chicle_next_solver_count")
+    return int(rc)
 
 
 class ChicleRound:

@@ -1048,6 +1048,15 @@ double chicle_projected_iteration_time(int32_t K_tasks, int32_t nodes, int32_t n
     return projected_iteration_time(K_tasks, nodes, n_slow, slow_factor, base_nodes);
 }
 
+int32_t chicle_next_solver_count(const double *gap, int32_t n_gaps, int32_t K, int32_t K_min,
+                                 double stall_ratio, int32_t patience, int32_t since_change)
+{
+    if (!gap || n_gaps < 1 || K < 1 || K_min < 1 || !(stall_ratio > 0.0 && stall_ratio <= 1.0) ||
+        patience < 1 || since_change < 0)
+        return -1;
+    return next_solver_count(gap, n_gaps, K, K_min, stall_ratio, patience, since_change);
+}
+
 static bool table_ok(const int32_t *t, int32_t n_chunks, int32_t K)
 {
     if (!t || n_chunks < 0 || K <= 0) return false;

@@ -36,6 +36,19 @@ inline double projected_iteration_time(int K_tasks, int nodes, int n_slow, doubl
     return best;
 }
 
+// When to scale in (Section 2.2: start with many partitions and reduce them after a few iterations; the
+// evaluation's summary: scale in when convergence slows down).  A round has stalled when it left more
+// than stall_ratio of the gap it started from; after `patience` stalled rounds in a row, all run with
+// the current K, the number of solvers is halved (rounded up, never below K_min).
+inline int next_solver_count(const double *gap, int n_gaps, int K, int K_min, double stall_ratio, int patience,
+                             int since_change)
+{
+    if (K <= K_min || since_change < patience || n_gaps < patience + 1) return K;
+    for (int t = n_gaps - patience; t < n_gaps; ++t)
+        if (!(gap[t] > stall_ratio * gap[t - 1])) return K;
+    return std::max(K_min, (K + 1) / 2);
+}
+
 // Scale-out: solvers K_old .. K_new-1 are new.  Every old solver hands over
 // floor(count * (K_new - K_old) / K_new) of its chunks, those with the smallest draw (ties: smaller
 // chunk id); the handed-over chunks, taken old solver by old solver in pick order, are dealt to the

@@ -18,13 +18,14 @@ from typing import Callable, Dict, List, Optional, Sequence
 
 import numpy as np
 
-from .binding import ChicleRound, balance, projected_iteration_time, scale_in, scale_out
+from .binding import ChicleRound, balance, next_solver_count, projected_iteration_time, scale_in, scale_out
 
 
 def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], list], target_rel: float,
                max_rounds: int, min_rounds: int = 0, table: Optional[np.ndarray] = None,
                device: str = "cuda:0", schedule: Optional[Sequence] = None,
-               draws: Optional[Callable[[int, int], np.ndarray]] = None) -> Dict:
+               draws: Optional[Callable[[int, int], np.ndarray]] = None,
+               adaptive: Optional[Dict] = None) -> Dict:
     """Rounds with a constant number of solvers K from alpha = 0, w = 0 until the duality gap has
     fallen to `target_rel` times its initial value (or `max_rounds`).
 
@@ -36,7 +37,10 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
     schedule: optional [(round, K), ...] changes of the number of solvers before the given rounds
     (Section 2.2 cites that starting with many partitions and reducing them after a few iterations
     speeds up convergence): fewer solvers through the scale-in policy, more through the scale-out policy
-    with draws(round, n_chunks) as its random words.  K is then the first entry's solver count."""
+    with draws(round, n_chunks) as its random words.  K is then the first entry's solver count.
+
+    adaptive: {"K_min", "stall_ratio", "patience"}: after every round `chicle_next_solver_count` decides
+    from the gaps so far whether to halve the number of solvers (scale-in policy) before the next one."""
     import torch
     changes = dict(schedule or [])
     g = ChicleRound.from_problem(problem, max_solvers=max([K] + list(changes.values())), device=device)
@@ -52,6 +56,7 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
         block = 16                                  # orders are generated and uploaded in blocks
         elapsed = 0.0
         r = 0
+        since_change = 0
         while r < max_rounds and (reached is None or r < min_rounds):
             if r in changes and changes[r] != K:
                 K_new = changes[r]
@@ -60,6 +65,7 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
                 K = K_new
                 g.assign(K, table)
                 rows = g.solver_rows()
+                since_change = 0
             nxt = min([c for c in changes if c > r] or [max_rounds])
             n_blk = min(block, max_rounds - r, nxt - r)
             dev = [g.upload_perm(permutations(r + i, rows)) for i in range(n_blk)]
@@ -73,10 +79,17 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
                 gaps.append(gap)
                 ks.append(K)
                 r += 1
+                since_change += 1
                 if reached is None and gap <= target_rel * g0:
                     reached, t_reached = r, elapsed
                 if reached is not None and r >= min_rounds:
                     break
+                if adaptive:
+                    K_new = next_solver_count(gaps, K, adaptive["K_min"], adaptive["stall_ratio"],
+                                              adaptive["patience"], since_change)
+                    if K_new != K:                  # orders uploaded for later rounds no longer fit
+                        changes[r] = K_new
+                        break
         return {"K": ks[0], "K_per_round": ks[1:], "gaps": gaps, "rounds_to_target": reached, "seconds_to_target": t_reached,
                 "seconds": elapsed, "rounds": r}
     finally:
@@ -110,6 +123,9 @@ def main(argv=None) -> int:
     ap.add_argument("--nodes", type=int, nargs="+", default=[16, 14, 8])
     ap.add_argument("--target", type=float, default=1e-3, help="gap relative to the initial gap")
     ap.add_argument("--max-rounds", type=int, default=200)
+    ap.add_argument("--adaptive", nargs=4, default=None, metavar=("K0", "K_MIN", "STALL_RATIO", "PATIENCE"),
+                    help="one more run that starts with K0 solvers and halves them whenever PATIENCE rounds in a row "
+                         "left more than STALL_RATIO of the gap, e.g. 64 8 0.75 1")
     ap.add_argument("--schedule", nargs="*", default=[], metavar="ROUND:K",
                     help="one more run that changes the number of solvers before the given rounds, e.g. 0:64 3:32 6:16")
     args = ap.parse_args(argv)
@@ -133,7 +149,16 @@ def main(argv=None) -> int:
         print("schedule %s: rounds to target %s, %.1f ms to target" %
               (sched, scheduled["rounds_to_target"], 1e3 * (scheduled["seconds_to_target"] or float("nan"))),
               file=sys.stderr, flush=True)
+    adaptive = None
+    if args.adaptive:
+        K0, K_min, ratio, patience = int(args.adaptive[0]), int(args.adaptive[1]), float(args.adaptive[2]), int(args.adaptive[3])
+        adaptive = run_to_gap(p, K0, lambda r, rows: round_permutations(cfg["seed"], r, rows), args.target,
+                              args.max_rounds, adaptive={"K_min": K_min, "stall_ratio": ratio, "patience": patience})
+        print("adaptive from K=%d (floor %d, stall ratio %g, patience %d): solvers per round %s, rounds to target %s, "
+              "%.1f ms to target" % (K0, K_min, ratio, patience, adaptive["K_per_round"], adaptive["rounds_to_target"],
+                                     1e3 * (adaptive["seconds_to_target"] or float("nan"))), file=sys.stderr, flush=True)
     out = {"workload": "%s/%s" % (args.workload, args.size), "target_rel": args.target,
+           "adaptive": None if adaptive is None else {k: v for k, v in adaptive.items() if k != "gaps"},
            "scheduled": None if scheduled is None else {k: v for k, v in scheduled.items() if k != "gaps"},
            "runs": [{k: v for k, v in r.items() if k != "gaps"} for r in results],
            "gaps": {str(r["K"]): r["gaps"] for r in results},

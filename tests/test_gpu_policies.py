@@ -157,6 +157,38 @@ def test_scale_in_schedule_run_matches_oracle(mods):
         assert abs(a - b) <= 1e-3 * abs(b)
 
 
+def test_gap_driven_scale_in_run_matches_oracle(mods):
+    """Solvers halved whenever a round leaves more than 0.8 of the gap: the driver's run, deciding through
+    the library from the library's gaps, against the oracle deciding from its own.  The ratios at the
+    decisions are far from the threshold (0.20, 0.90, 1.24), so both must take the same decisions."""
+    oracle_mod, binding = mods
+    from paper_1909_04885_amd import sweep
+    cfg, p = cached_problem("sparse_zipf", "mini")
+    print("\ncase sparse_zipf mini, gap-driven scale-in from 8 solvers", flush=True)
+    rule, rounds = {"K_min": 2, "stall_ratio": 0.8, "patience": 1}, 8
+    res = sweep.run_to_gap(p, 8, lambda r, rows: round_permutations(cfg["seed"], r, rows), 1e-9,
+                           max_rounds=rounds, adaptive=rule)
+    o = oracle_mod.OracleCoCoA.from_problem(p)
+    K, table = 8, oracle_mod.assign_greedy(p.chunk_nnz(), 8).tolist()
+    o.assign(K, np.asarray(table, dtype=np.int32))
+    ref, ks, since = [o.gap()[2]], [], 0
+    for r in range(rounds):
+        o.local_epoch(round_permutations(cfg["seed"], r, o.rows_per_solver()))
+        o.aggregate()
+        ref.append(o.gap()[2])
+        ks.append(K)
+        since += 1
+        K_new = opol.next_solver_count(ref, K, rule["K_min"], rule["stall_ratio"], rule["patience"], since)
+        if K_new != K:
+            table = opol.scale_in(table, K, K_new)
+            K, since = K_new, 0
+            o.assign(K, np.asarray(table, dtype=np.int32))
+    print("solvers", res["K_per_round"], "gaps", ["%.4f" % x for x in res["gaps"]], flush=True)
+    assert ks == [8, 8, 4, 2, 2, 2, 2, 2] and res["K_per_round"] == ks
+    for a, b in zip(res["gaps"], ref):
+        assert abs(a - b) <= 1e-3 * abs(b)
+
+
 @pytest.mark.parametrize("K", [1, 17])
 def test_odd_solver_counts_with_the_batched_solver(mods, K):
     """Solver counts that are not a multiple of the number of L2 partitions (the batched solver pairs every

@@ -204,3 +204,37 @@ def test_projection_special_cases(oracle_mod):
             assert oracle_mod.projected_round_time(K, N, slow_factor=1.5, n_slow=N) == pytest.approx(1.5 * eq)
             assert oracle_mod.projected_round_time(K, N, slow_factor=1.0, n_slow=N // 2) == pytest.approx(eq)
             assert oracle_mod.projected_round_time(None, N, slow_factor=2.0, n_slow=N) == pytest.approx(2.0 * 16 / N)
+
+
+def test_scale_in_trigger_hand_worked():
+    """Gaps 1, .5, .45, .43: rounds 2 and 3 each left more than 0.8 of their gap.  With patience 2 the
+    change comes after round 3, not earlier, and only if both rounds ran with the current K."""
+    g = [1.0, 0.5, 0.45, 0.43]
+    assert opol.next_solver_count(g[:2], 64, 8, 0.8, 1, 1) == 64          # 0.5 of the gap left: progress
+    assert opol.next_solver_count(g[:3], 64, 8, 0.8, 1, 2) == 32          # 0.9 left: stalled
+    assert opol.next_solver_count(g[:3], 64, 8, 0.8, 2, 2) == 64          # only one of the last two stalled
+    assert opol.next_solver_count(g, 64, 8, 0.8, 2, 3) == 32
+    assert opol.next_solver_count(g, 64, 8, 0.8, 2, 1) == 64              # K changed one round ago
+    assert opol.next_solver_count(g, 9, 8, 0.8, 1, 3) == 8                # never below the floor
+    assert opol.next_solver_count(g, 8, 8, 0.8, 1, 3) == 8
+    assert opol.next_solver_count(g, 5, 1, 0.8, 1, 3) == 3                # halves round up
+    assert opol.next_solver_count([1.0], 64, 8, 0.8, 1, 0) == 64          # no round yet
+    assert opol.next_solver_count([1.0, 1.5], 64, 8, 0.8, 1, 1) == 32     # a gap that grew has stalled
+
+
+def test_library_scale_in_trigger_matches_oracle(chicle):
+    rng = np.random.default_rng(13)
+    for _ in range(300):
+        n = int(rng.integers(1, 12))
+        g = np.cumprod(np.concatenate([[1.0], rng.choice([0.3, 0.7, 0.79, 0.81, 0.95, 1.1], n - 1)])) if n > 1 else np.array([1.0])
+        K, K_min = int(rng.integers(1, 70)), int(rng.integers(1, 20))
+        ratio = float(rng.choice([0.5, 0.8, 1.0]))
+        patience, since = int(rng.integers(1, 4)), int(rng.integers(0, 6))
+        assert chicle.next_solver_count(g, K, K_min, ratio, patience, since) == \
+            opol.next_solver_count(g.tolist(), K, K_min, ratio, patience, since)
+    for bad in [dict(K=0), dict(K_min=0), dict(stall_ratio=0.0), dict(stall_ratio=1.5), dict(patience=0),
+                dict(since_change=-1)]:
+        args = dict(gaps=[1.0, 0.9], K=4, K_min=2, stall_ratio=0.8, patience=1, since_change=1)
+        args.update(bad)
+        with pytest.raises(chicle.ChicleError):
+            chicle.next_solver_count(**args)
