@@ -295,3 +295,41 @@ def test_set_state_resumes_a_run(mods):
     for k in range(K):
         assert np.linalg.norm(g.get_delta_w(k) - dws[k]) <= TOL_DW * np.linalg.norm(dws[k])
     g.close()
+
+
+@pytest.mark.parametrize("loss", ["hinge", "squared", "logistic"])
+@pytest.mark.parametrize("shared", [0, 40])
+def test_mixed_row_lengths(mods, loss, shared):
+    """Rows from empty to 9000 entries in one visiting order (the row-wise solver keeps a fixed number of a
+    row's entries in registers and streams the rest), columns spread over 300 000, and `shared` columns that
+    every row of more than 20 entries carries as well."""
+    oracle_mod, binding = mods
+    from workloads.generate import Problem
+    g = np.random.default_rng(17 + shared)
+    n, d, K = 230, 300000, 2
+    lens = g.choice([0, 3, 17, 60, 300, 1000, 1500, 2500], size=n, p=[.03, .1, .1, .17, .2, .2, .1, .1])
+    lens[[20, 21]] = [5000, 9000]
+    lens[7] = 4096
+    common = g.choice(d, size=shared, replace=False)
+    cols, vals = [], []
+    for L in lens:
+        c = g.choice(d, size=int(L), replace=False)
+        if L > 20 and shared:
+            c = np.unique(np.concatenate([c[:int(L) - shared], common]))
+        c.sort()
+        v = g.standard_normal(c.size)
+        cols.append(c.astype(np.int32))
+        vals.append((v / max(np.linalg.norm(v), 1e-30)).astype(np.float32))
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum([c.size for c in cols], out=rp[1:])
+    y = g.standard_normal(n).astype(np.float32) if loss == "squared" else np.where(g.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    bounds = np.array([0, 50, 51, 120, 200, n], dtype=np.int64)
+    p = Problem("mixed", loss, n, d, 0.02, y, bounds, row_ptr=rp, col=np.concatenate(cols), val=np.concatenate(vals))
+    print("\ncase mixed row lengths %s shared=%d entries=%d" % (loss, shared, int(rp[-1])), flush=True)
+    cfg = {"seed": 5, "rounds": 4, "schedule": [(0, K)], "K": K}
+    table = (np.arange(p.n_chunks) % K).astype(np.int32)
+    # with so few rows over so many columns the logistic case is at its optimum after two rounds (Delta w
+    # falls 20-fold per round); from the fourth on the fp32 cancellation in a' - a shows in the relative error
+    rounds = 3 if loss == "logistic" else 4
+    run_lockstep(cfg, p, oracle_mod, binding, rounds=rounds, check_alpha_every=1, log=_log,
+                 tables=lambda r, Kp, tp: (K, table, table.copy()) if r == 0 else None, max_solvers=K)
