@@ -157,7 +157,10 @@ def main():
         "local_epoch": {"ms": epoch_ms, "nnz_per_s": p.nnz / (epoch_ms * 1e-3),
                         "coord_updates_per_s": p.n / (epoch_ms * 1e-3),
                         "gram_ms": float(np.mean(seg_ms["epoch_gram"])) if seg_ms["epoch_gram"] else None,
-                        "chain_ms": float(np.mean(seg_ms["epoch_chain"])) if seg_ms["epoch_chain"] else None},
+                        "chain_ms": float(np.mean(seg_ms["epoch_chain"])) if seg_ms["epoch_chain"] else None,
+                        # the dependency chain: a solver's coordinate steps come one after the other
+                        "max_rows_per_solver": int(max(rows)),
+                        "ns_per_step_of_longest_solver": epoch_ms * 1e6 / max(int(max(rows)), 1)},
         "aggregate": {"ms": agg_ms, "GB_per_s": agg_bytes / (agg_ms * 1e-3) / 1e9,
                       "frac_hbm_peak": agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "gap": {"ms": gap_ms, "GB_per_s": gap_bytes / (gap_ms * 1e-3) / 1e9,
