@@ -38,7 +38,8 @@
  *     are renumbered by popularity (done once, at the first assign), which the get/set calls undo;
  *   - the library allocates no device memory: it carves everything out of the arena handed to
  *     chicle_create (size it with chicle_arena_bytes); the arena and the HIP stream are borrowed for
- *     the lifetime of the context; all work is enqueued on that stream;
+ *     the lifetime of the context; all work is enqueued on that stream; the context itself holds 32 bytes
+ *     of pinned host memory, into which the gap's last kernel writes its sums;
  *   - calls that return values to the host (gap, get_*) wait for the stream; the others only enqueue;
  *   - a context is not thread-safe.
  */

@@ -271,10 +271,11 @@ __global__ __launch_bounds__(256) void wsq_partial(const double *__restrict__ w,
     block_sum2_store(s, 0.0, &part_wsq[blockIdx.x], &part_unused[blockIdx.x]);
 }
 
-// out[0] = sum loss, out[1] = sum conj, out[2] = |w|^2; one workgroup, fixed summation order.
+// out[0] = sum loss, out[1] = sum conj, out[2] = |w|^2, out[3] = the kernels' error flag; one workgroup,
+// fixed summation order.  out may be host memory mapped into the device's address space.
 __global__ __launch_bounds__(256) void gap_finish(const double *part_loss, const double *part_conj,
                                                   int n_row_parts, const double *part_wsq,
-                                                  int n_w_parts, double *out)
+                                                  int n_w_parts, const int *err, double *out)
 {
     double a = 0.0, b = 0.0, c = 0.0;
     for (int i = threadIdx.x; i < n_row_parts; i += 256) { a += part_loss[i]; b += part_conj[i]; }
@@ -288,6 +289,7 @@ __global__ __launch_bounds__(256) void gap_finish(const double *part_loss, const
         out[0] = ra[0] + ra[1] + ra[2] + ra[3];
         out[1] = rb[0] + rb[1] + rb[2] + rb[3];
         out[2] = rc[0] + rc[1] + rc[2] + rc[3];
+        out[3] = (double)*err;
     }
 }
 

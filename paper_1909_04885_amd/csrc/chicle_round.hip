@@ -86,8 +86,9 @@ struct chicle_ctx {
     int32_t n_tiles = 0;
     bool zw_valid = true;      // the rows' residuals match w (set at load time for w = 0)
     int32_t *perm_stage = nullptr;
-    double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr,
-           *gap_out = nullptr;
+    double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr;
+    double *gap_host = nullptr;       // 4 doubles of pinned host memory the gap's last kernel writes into ...
+    double *gap_host_dev = nullptr;   // ... through this device address
     int *err_dev = nullptr;
     int *progress_dev = nullptr;      // per solver: block its batched pass has reached
     long long *ticks_dev = nullptr;   // 2 per solver: clock at start / end of its last pass
@@ -159,7 +160,6 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, row -> chunk
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);               // chunk_first, list_base
     s += 2 * align_up(sizeof(double) * (size_t)std::max(GAP_PARTS, 2 * n_chunks)) + 2 * align_up(sizeof(double) * WSQ_PARTS);
-    s += align_up(sizeof(double) * 4);
     s += align_up(sizeof(int));
     s += align_up(sizeof(long long) * 2 * (size_t)max_solvers);
     s += align_up(sizeof(int) * (size_t)max_solvers);
@@ -561,7 +561,6 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->part_conj = (double *)carve(c, sizeof(double) * (size_t)c->gap_parts);
     c->part_wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
     c->part_unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
-    c->gap_out = (double *)carve(c, sizeof(double) * 4);
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
@@ -583,6 +582,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     }
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&c->gap_host, sizeof(double) * 4, hipHostMallocMapped) == hipSuccess &&
+         hipHostGetDevicePointer((void **)&c->gap_host_dev, c->gap_host, 0) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
          hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
          hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
@@ -930,13 +931,19 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
     hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, c->part_wsq, c->part_unused);
     hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, c->part_loss, c->part_conj, grid,
-                       c->part_wsq, gw, c->gap_out);
+                       c->part_wsq, gw, c->err_dev, c->gap_host_dev);
     seg_end(c, CHICLE_SEG_GAP);
     HIP_TRY(c, hipGetLastError());
-    double h[3];
-    HIP_TRY(c, hipMemcpyAsync(h, c->gap_out, sizeof h, hipMemcpyDeviceToHost, c->stream));
-    rc = check_deferred(c);   // synchronises
-    if (rc) return rc;
+    // the sums and the error flag arrive in pinned host memory with the end of the kernel: no copy to wait for
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const double *h = c->gap_host;
+    if (h[3] != 0.0) {
+        const int flag = (int)h[3];
+        HIP_TRY(c, hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream));
+        if (flag & ERR_PERM_RANGE)
+            return fail(c, CHICLE_EDEVICE, "a visiting-order entry was outside [0, rows of its solver)");
+        return fail(c, CHICLE_EDEVICE, "kernel error flag %d", flag);
+    }
     const double n = (double)c->n_total;
     const double P = 0.5 * c->lambda * h[2] + h[0] / n;
     const double D = -0.5 * c->lambda * h[2] - h[1] / n;
@@ -1147,6 +1154,7 @@ void chicle_destroy(chicle_ctx *c)
     if (!c) return;
     if (c->side) (void)hipStreamSynchronize(c->side);
     (void)hipStreamSynchronize(c->stream);
+    if (c->gap_host) (void)hipHostFree(c->gap_host);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
