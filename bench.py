@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-time-to-gap", action="store_true")
     ap.add_argument("--gap-round-cap", type=int, default=100)
+    ap.add_argument("--scale-in-from", type=int, default=0, metavar="K0",
+                    help="also time the run to the gap target that starts with K0 solvers and scales in as rounds stall")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (untimed), as a reference for HBM byte counters")
     args = ap.parse_args()
@@ -184,6 +186,16 @@ def main():
                               "ms": None if res["seconds_to_target"] is None else 1e3 * res["seconds_to_target"],
                               "round_cap": args.gap_round_cap, "final_gap": res["gaps"][-1],
                               "initial_gap": res["gaps"][0]}
+        if args.scale_in_from and args.scale_in_from > K:
+            # the same target with the number of solvers chosen as the run goes: start with more solvers
+            # and halve them whenever a round leaves more than 3/4 of the gap (never below K / 4)
+            rule = {"K_min": max(K // 4, 1), "stall_ratio": 0.75, "patience": 1}
+            res = run_to_gap(p, args.scale_in_from, lambda r, rws: round_permutations(cfg["seed"], r, rws), 1e-3,
+                             max_rounds=args.gap_round_cap, adaptive=rule)
+            out["time_to_gap_scale_in"] = {
+                "rule": dict(rule, K_start=args.scale_in_from), "rounds": res["rounds_to_target"],
+                "ms": None if res["seconds_to_target"] is None else 1e3 * res["seconds_to_target"],
+                "solvers_per_round": res["K_per_round"][:res["rounds_to_target"] or None]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(p, cfg, table, K)
     print(json.dumps(out), flush=True)
