@@ -120,14 +120,17 @@ def main():
     def nxt(r):
         return perms[r + 1] if r + 1 < total else None
 
+    def cur(r):                            # every round but the first runs with the orders announced before it
+        return perms[r] if r == 0 else None
+
     for r in range(args.warmup):
-        g.local_epoch_ahead(perms[r], nxt(r)); g.aggregate(); g.gap()
+        g.local_epoch_ahead(cur(r), nxt(r)); g.aggregate(); g.gap()
     torch.cuda.synchronize()
     seg_ms = {"local_epoch": [], "aggregate": [], "gap": [], "epoch_gram": [], "epoch_chain": []}
     gaps = []
     t_start = time.perf_counter()
     for r in range(args.warmup, total):
-        g.local_epoch_ahead(perms[r], nxt(r))     # announces the next round's orders (all are in HBM)
+        g.local_epoch_ahead(cur(r), nxt(r))       # announces the next round's orders (all are in HBM)
         g.aggregate()
         gaps.append(g.gap()[2])          # synchronises: the three scalars come back to the host
         for s in seg_ms:                  # events of this round have completed

@@ -179,8 +179,10 @@ int chicle_rebalance(const int64_t *chunk_load, int32_t n_chunks, int32_t K, con
 int32_t chicle_next_solver_count(const double *gap, int32_t n_gaps, int32_t K, int32_t K_min,
                                  double stall_ratio, int32_t patience, int32_t since_change);
 
-/* Scheduler step between iterations: give every chunk to one of K solvers (host table of n_chunks
- * entries in [0, K)); sigma becomes K; every solver's private vector is re-seeded with w.  A solver
+/* Scheduler step between iterations (Section 3 "Uni-tasks": between iterations the scheduler owns the
+ * chunks and may hand them to other tasks; Section 5.1: sigma is the number of tasks): give every chunk
+ * to one of K solvers (host table of n_chunks entries in [0, K)); sigma becomes K; every solver's
+ * update starts from nothing (its private vector equals w).  A solver
  * may own no chunk.  alpha is not touched.  A solver's local rows are its chunks in ascending chunk id,
  * rows ascending inside a chunk.  Legal in LOADING (all chunks loaded, row counts summing to n_total)
  * and READY.  Errors: EINVAL, ESTATE. */
@@ -200,30 +202,38 @@ int chicle_set_solver(chicle_ctx *ctx, int32_t kind);
 
 /* One local pass of all K solvers, concurrently, each from the current w (Section 2.2; Section 4.2).
  * perm_device: device array of n_total int32: solver 0's visiting order (a permutation of
- * [0, rows_0)), then solver 1's, and so on.  Commits alpha in the chunks and leaves
- * v_k = w + sigma * Delta w_k in each solver's private vector.  READY -> EPOCH_DONE.
+ * [0, rows_0)), then solver 1's, and so on.  Commits alpha in the chunks and leaves the solver's update
+ * in its private vector, which is stored as the difference u_k = v_k - w = sigma * Delta w_k (v_k being
+ * the solver's private copy of the shared vector).  READY -> EPOCH_DONE.
  * An out-of-range perm entry is skipped and reported as EDEVICE by the next synchronising call. */
 int chicle_local_epoch(chicle_ctx *ctx, const int32_t *perm_device);
 
-/* Same, and perm_next_device (may be NULL) announces the orders of the following local pass: work for it
- * that depends on the data and the orders alone (the Gram blocks of the batched solver) is started on a
- * stream of the library's own, ordered after everything enqueued on the context's stream before this call,
- * and runs beside this pass.  It is used if the next call passes the same pointer as perm_device with
- * unchanged contents; otherwise it is discarded (an assign discards it too). */
+/* Same, and perm_next_device (may be NULL) announces the orders of the following local pass.  They are
+ * copied into the context on the context's stream (the caller's buffer is an ordinary stream-ordered input
+ * of this call and is not referred to afterwards), and work for that pass which depends on the data and the
+ * orders alone (the Gram blocks of the batched solver) is started on a stream of the library's own, ordered
+ * after everything enqueued on the context's stream before this call, and runs beside this pass.
+ * perm_device may be NULL: the pass then runs with the orders that the previous call announced, from the
+ * context's copy, and uses the work prepared for them.  A non-NULL perm_device discards what was announced;
+ * so does an assign.  Errors: EINVAL (perm_device NULL with nothing announced), ESTATE. */
 int chicle_local_epoch_ahead(chicle_ctx *ctx, const int32_t *perm_device, const int32_t *perm_next_device);
 
 /* Same as chicle_local_epoch with the orders given as a host array (copied to a staging area first). */
 int chicle_local_epoch_host_perm(chicle_ctx *ctx, const int32_t *perm_host);
 
 /* Trainer step (Section 4.1: merge updates, broadcast the model): w <- w + sum_k Delta w_k, then every
- * private vector <- w.  EPOCH_DONE -> READY. */
+ * solver's private copy equals w again (its stored difference u_k is cleared).  EPOCH_DONE -> READY. */
 int chicle_aggregate(chicle_ctx *ctx);
 
-/* P(w), D(alpha) and P - D at the current state (host outs, any may be NULL).  Legal in READY.
- * Synchronises. */
+/* The convergence metric that solvers report to the trainer every iteration (Section 4.1) and that the
+ * evaluation follows, the duality gap (Section 5.1): P(w), D(alpha) and P - D at the current state, with the
+ * objectives stated at the top of this file (host outs, any may be NULL).  Legal in READY.  Synchronises.
+ * Errors: ESTATE, EDEVICE. */
 int chicle_gap(chicle_ctx *ctx, double *primal, double *dual, double *gap);
 
-/* State access (host arrays of d floats / n_rows-of-that-chunk floats).  get_* synchronise.
+/* State access: the shared vector, and the per-sample state that lives inside its chunk and moves with it
+ * (Section 4.4 "In-memory chunk data format"); what a trainer checkpoints or restores between iterations.
+ * Host arrays of d floats / n_rows-of-that-chunk floats.  get_* synchronise.
  * set_alpha is legal in READY/LOADING, set_w in READY; get_delta_w in EPOCH_DONE only:
  * solver >= 0 gives Delta w_solver = (v_solver - w)/sigma, solver = -1 gives sum_k Delta w_k. */
 int chicle_get_w(chicle_ctx *ctx, float *w_out);

@@ -293,8 +293,10 @@ class ChicleRound:
         self._check(self._L.chicle_local_epoch(self._h, self._perm_ptr(perm_device)))
 
     def local_epoch_ahead(self, perm_device, perm_next_device=None):
+        """perm_device None: run with the orders the previous call announced (the library kept a copy)."""
+        cur = None if perm_device is None else self._perm_ptr(perm_device)
         nxt = None if perm_next_device is None else self._perm_ptr(perm_next_device)
-        self._check(self._L.chicle_local_epoch_ahead(self._h, self._perm_ptr(perm_device), nxt))
+        self._check(self._L.chicle_local_epoch_ahead(self._h, cur, nxt))
 
     def local_epoch_host_perm(self, perm_host):
         flat = _host(perm_host, np.int32)

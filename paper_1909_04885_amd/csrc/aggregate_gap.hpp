@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
 // only the rare columns go to the cache hierarchy.  1024 threads; dynamic LDS = n_hot * sizeof(WT).
 constexpr int GAP_HOT_THREADS = 1024;
 constexpr int GAP_HOT_BYTES = 48 * 1024;
-constexpr int GAP_HOT_LPR = 16;             // lanes per row; a lane takes 4 consecutive entries
+constexpr int GAP_HOT_MAX_LPR = 16;         // lanes per row at most; a lane takes 4 consecutive entries
 
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkDev *__restrict__ chunks,
@@ -170,23 +170,30 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
     extern __shared__ __align__(16) unsigned char gap_hot_raw[];
     WT *hot = reinterpret_cast<WT *>(gap_hot_raw);
     __shared__ double ra[GAP_HOT_THREADS / 64], rb[GAP_HOT_THREADS / 64];
-    constexpr int GROUPS = GAP_HOT_THREADS / LPR;
-    const int sub = threadIdx.x % LPR;
-    const int grp = threadIdx.x / LPR;
+    // LPR lanes per row, as many whole rows per wavefront as fit (LPR need not divide 64: with rows of 40
+    // entries ten lanes carry a row and six rows share a wavefront; the lanes left over idle)
+    constexpr int ROWS_PER_WAVE = 64 / LPR;
+    constexpr int GROUPS = (GAP_HOT_THREADS / 64) * ROWS_PER_WAVE;
+    const int lane = threadIdx.x & 63;
+    const int sub = lane % LPR;
+    const bool idle = lane >= ROWS_PER_WAVE * LPR;
+    const int grp = (threadIdx.x >> 6) * ROWS_PER_WAVE + lane / LPR;
     const ChunkDev &ch = chunks[blockIdx.y];
     const int n_rows = ch.n_rows;
     const int32_t *__restrict__ rp = ch.row_ptr;
     const int32_t *__restrict__ col = ch.col;
     const float *__restrict__ val = ch.val;
     const int stride = gridDim.x * GROUPS;
-    const int first = blockIdx.x * GROUPS + grp;
     for (int i = threadIdx.x; i < n_hot; i += GAP_HOT_THREADS) hot[i] = w[i];
     __syncthreads();
     double s_loss = 0.0, s_conj = 0.0;
-    for (int r0 = first; r0 < n_rows; r0 += 2 * stride) {
+    // (the trip count is the same for all lanes of a wavefront: the shuffles below need every lane)
+    for (int rb = blockIdx.x * GROUPS; rb < n_rows; rb += 2 * stride) {
+        const int r0 = rb + grp;
         const int r1 = r0 + stride;
-        const bool two = r1 < n_rows;
-        const int b0 = rp[r0], e0 = rp[r0 + 1];
+        const bool one = !idle && r0 < n_rows;
+        const bool two = !idle && r1 < n_rows;
+        const int b0 = one ? rp[r0] : 0, e0 = one ? rp[r0 + 1] : 0;
         const int b1 = two ? rp[r1] : 0, e1 = two ? rp[r1 + 1] : 0;
         WT z0 = 0, z1 = 0;
         // Each lane takes 4 consecutive entries of its row with one 16-byte load per array (the vector
@@ -214,10 +221,14 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
                 z1 += (WT)v1[k] * w1[k];
             }
         }
+        // sum over the row's lanes into its first lane
 #pragma unroll
-        for (int o = LPR / 2; o > 0; o >>= 1) { z0 += __shfl_xor(z0, o, 64); z1 += __shfl_xor(z1, o, 64); }
+        for (int o = 8; o > 0; o >>= 1) {
+            const WT y0 = __shfl_down(z0, o, 64), y1 = __shfl_down(z1, o, 64);
+            if (sub < o && sub + o < LPR) { z0 += y0; z1 += y1; }
+        }
         if (sub == 0) {
-            gap_row_terms<LOSS, WT>(ch.st + r0, z0, s_loss, s_conj);
+            if (one) gap_row_terms<LOSS, WT>(ch.st + r0, z0, s_loss, s_conj);
             if (two) gap_row_terms<LOSS, WT>(ch.st + r1, z1, s_loss, s_conj);
         }
     }

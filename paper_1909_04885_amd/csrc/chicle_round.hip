@@ -46,6 +46,12 @@ struct Seg {
     bool recorded = false;
 };
 
+// Partial sums of the gap kernels: one (loss, conjugate) pair per workgroup of the row pass, |w|^2 partials.
+struct GapScratch {
+    double *loss = nullptr, *conj = nullptr, *wsq = nullptr, *unused = nullptr;
+    int parts = 0;            // length of loss[] and conj[]
+};
+
 }  // namespace
 
 struct chicle_ctx {
@@ -79,14 +85,19 @@ struct chicle_ctx {
     int tile_buf = 0;                       // set the next chain kernel reads
     hipStream_t side = nullptr;             // stream of Gram kernels prepared ahead
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    const int32_t *ahead_perm = nullptr;    // visiting orders whose tiles are in tiles[1 - tile_buf] (side stream)
+    // Visiting orders announced for the next pass are copied here when they are announced (two buffers: the
+    // running pass may itself read announced orders), so the caller's buffer is not referred to afterwards.
+    int32_t *perm_ahead[2] = {nullptr, nullptr};
+    int ahead_buf = 0;                      // buffer the next announcement goes to
+    bool ahead_valid = false;               // perm_ahead[1 - ahead_buf] holds the orders of the next pass
+    bool ahead_tiles = false;               // ... and their Gram tiles are in tiles[1 - tile_buf] (side stream)
     int32_t *tile_solver_dev = nullptr;
     int32_t *row_chunk_dev = nullptr, *chunk_first_dev = nullptr, *list_base_dev = nullptr;
     int64_t max_tiles = 0;
     int32_t n_tiles = 0;
     bool zw_valid = true;      // the rows' residuals match w (set at load time for w = 0)
     int32_t *perm_stage = nullptr;
-    double *part_loss = nullptr, *part_conj = nullptr, *part_wsq = nullptr, *part_unused = nullptr;
+    GapScratch gap_scratch;           // in the arena
     double *gap_host = nullptr;       // 4 doubles of pinned host memory the gap's last kernel writes into ...
     double *gap_host_dev = nullptr;   // ... through this device address
     int *err_dev = nullptr;
@@ -105,7 +116,6 @@ struct chicle_ctx {
     std::vector<SolverDev> solvers;
     int max_list = 0;
     int gap_lpr = 64, gap_items = 0, gap_hot_grid = 0;
-    int gap_parts = 0;         // length of the partial-sum arrays of the gap row kernels
 
     bool profiling = false;
     Seg seg[CHICLE_SEG_COUNT];
@@ -157,7 +167,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
     s += 2 * align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
     s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
-    s += 2 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, row -> chunk
+    s += 4 * align_up(sizeof(int32_t) * (size_t)n_total);                // perm staging, announced orders (2), row -> chunk
     s += 2 * align_up(sizeof(int32_t) * (size_t)n_chunks);               // chunk_first, list_base
     s += 2 * align_up(sizeof(double) * (size_t)std::max(GAP_PARTS, 2 * n_chunks)) + 2 * align_up(sizeof(double) * WSQ_PARTS);
     s += align_up(sizeof(int));
@@ -322,21 +332,21 @@ int launch_gram(chicle_ctx *c, const int32_t *perm, int buf, hipStream_t stream)
 // on the side stream so that they run beside this pass's chain kernel (which occupies K of the 256
 // compute units); they depend on the data and the orders only.
 template <int LOSS>
-int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
+int launch_batched(chicle_ctx *c, const int32_t *perm, bool tiles_ready, const int32_t *perm_next)
 {
     const RoundScalars sc = scalars(c);
     int rc;
-    if (c->ahead_perm != nullptr && c->ahead_perm == perm) {
+    if (tiles_ready) {
         c->tile_buf = 1 - c->tile_buf;
         HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
     } else {
-        if (c->ahead_perm) HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));   // unused, but let it finish
+        if (c->ahead_tiles) HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));   // unused, but let it finish
         seg_begin(c, CHICLE_SEG_EPOCH_GRAM);
         rc = launch_gram<LOSS>(c, perm, c->tile_buf, c->stream);
         seg_end(c, CHICLE_SEG_EPOCH_GRAM);
         if (rc) return rc;
     }
-    c->ahead_perm = nullptr;
+    c->ahead_tiles = false;
     if (perm_next) HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));   // everything enqueued so far
     const int ml = std::max(c->max_list, 1);
     const size_t hot_off = (sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + 15) & ~(size_t)15;
@@ -363,7 +373,7 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
         }
         if (rc) return rc;
         HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
-        c->ahead_perm = perm_next;
+        c->ahead_tiles = true;
     }
     return CHICLE_OK;
 }
@@ -372,69 +382,81 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, const int32_t *perm_next)
 int drop_ahead(chicle_ctx *c)
 {
     if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
-    c->ahead_perm = nullptr;
+    c->ahead_tiles = false;
+    c->ahead_valid = false;
     return CHICLE_OK;
 }
 
 template <int LOSS, int LPRG, typename WT>
-void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w)
+void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w, const GapScratch &gs)
 {
     const dim3 grid(grid_x, c->n_chunks);
     if (c->gap_hot_grid > 0) {
+        // lanes per row: the fewest that cover the longest row with 4 entries each
         const int n_hot = (int)std::min<int64_t>(c->d, GAP_HOT_BYTES / (int)sizeof(WT));
-        hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, GAP_HOT_LPR, WT>), dim3(c->gap_hot_grid, c->n_chunks),
-                           dim3(GAP_HOT_THREADS), n_hot * sizeof(WT), c->stream, c->chunks_dev, w, n_hot,
-                           c->part_loss, c->part_conj);
+        const dim3 hg(c->gap_hot_grid, c->n_chunks);
+        const size_t sh = n_hot * sizeof(WT);
+        const int need = (c->max_row_len + 3) / 4;
+#define CHICLE_GAP_HOT(L)                                                                                   \
+        hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, L, WT>), hg, dim3(GAP_HOT_THREADS), sh, c->stream,      \
+                           c->chunks_dev, w, n_hot, gs.loss, gs.conj)
+        if (need <= 4) CHICLE_GAP_HOT(4);
+        else if (need <= 8) CHICLE_GAP_HOT(8);
+        else if (need <= 10) CHICLE_GAP_HOT(10);
+        else if (need <= 12) CHICLE_GAP_HOT(12);
+        else CHICLE_GAP_HOT(16);
+#undef CHICLE_GAP_HOT
     } else if (c->dense)
         hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev,
-                           (int)c->d, w, c->part_loss, c->part_conj);
+                           (int)c->d, w, gs.loss, gs.conj);
     else
         hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev, w,
-                           c->part_loss, c->part_conj);
+                           gs.loss, gs.conj);
 }
 
 // Squared loss: dot products in double against the double w (its steps cancel y - z - alpha down to the
 // size of the update); logistic: in double as well (loss and conjugate nearly cancel in the gap close to
 // the optimum); hinge: float against the float mirror.
 template <int LOSS, int LPRG>
-void launch_gap_rows(chicle_ctx *c, int grid)
+void launch_gap_rows(chicle_ctx *c, int grid, const GapScratch &gs)
 {
-    if (LOSS != 0) launch_gap_rows_t<LOSS, LPRG, double>(c, grid, c->w64);
-    else launch_gap_rows_t<LOSS, LPRG, float>(c, grid, c->w);
+    if (LOSS != 0) launch_gap_rows_t<LOSS, LPRG, double>(c, grid, c->w64, gs);
+    else launch_gap_rows_t<LOSS, LPRG, float>(c, grid, c->w, gs);
 }
 
 template <int LOSS>
-void launch_gap_lpr(chicle_ctx *c, int grid)
+void launch_gap_lpr(chicle_ctx *c, int grid, const GapScratch &gs)
 {
     switch (c->gap_lpr) {
-        case 4: launch_gap_rows<LOSS, 4>(c, grid); break;
-        case 8: launch_gap_rows<LOSS, 8>(c, grid); break;
-        case 16: launch_gap_rows<LOSS, 16>(c, grid); break;
-        case 32: launch_gap_rows<LOSS, 32>(c, grid); break;
-        default: launch_gap_rows<LOSS, 64>(c, grid); break;
+        case 4: launch_gap_rows<LOSS, 4>(c, grid, gs); break;
+        case 8: launch_gap_rows<LOSS, 8>(c, grid, gs); break;
+        case 16: launch_gap_rows<LOSS, 16>(c, grid, gs); break;
+        case 32: launch_gap_rows<LOSS, 32>(c, grid, gs); break;
+        default: launch_gap_rows<LOSS, 64>(c, grid, gs); break;
     }
 }
 
 // The row pass of the gap: z_i = x_i . w into the chunks, loss and conjugate partial sums.
-int run_row_pass(chicle_ctx *c, int *grid_out)
+int run_row_pass(chicle_ctx *c, int *grid_out, const GapScratch &gs)
 {
     // workgroups per chunk: enough to fill the chip several times over, within the partial-sum arrays
     int max_rows = 1;
     for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
     const int rows_per_wg = 2 * (256 / c->gap_lpr);
     int gx = std::min((max_rows + rows_per_wg - 1) / rows_per_wg, std::max(1, 8192 / c->n_chunks));
-    gx = std::max(1, std::min(gx, c->gap_parts / c->n_chunks));
+    gx = std::max(1, std::min(gx, gs.parts / c->n_chunks));
     // popularity-numbered columns: frequent part of w from LDS, few large workgroups per chunk
     c->gap_hot_grid = 0;
-    if (c->renumbered && !c->dense && c->max_row_len <= 4 * GAP_HOT_LPR) {
-        const int rows_per_hot_wg = 2 * (GAP_HOT_THREADS / GAP_HOT_LPR);
+    if (c->renumbered && !c->dense && c->max_row_len <= 4 * GAP_HOT_MAX_LPR) {
+        const int lpr = std::max(4, (c->max_row_len + 3) / 4);
+        const int rows_per_hot_wg = 2 * (GAP_HOT_THREADS / 64) * (64 / lpr);
         gx = std::max(1, std::min(std::min(2, (max_rows + rows_per_hot_wg - 1) / rows_per_hot_wg),
-                                  c->gap_parts / c->n_chunks));
+                                  gs.parts / c->n_chunks));
         c->gap_hot_grid = gx;
     }
-    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx);
-    else if (c->loss == CHICLE_LOSS_SQUARED) launch_gap_lpr<1>(c, gx);
-    else launch_gap_lpr<2>(c, gx);
+    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx, gs);
+    else if (c->loss == CHICLE_LOSS_SQUARED) launch_gap_lpr<1>(c, gx, gs);
+    else launch_gap_lpr<2>(c, gx, gs);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = true;
     if (grid_out) *grid_out = gx * c->n_chunks;
@@ -553,14 +575,16 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->tiles[1] = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
     c->tile_solver_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->max_tiles);
     c->perm_stage = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
+    c->perm_ahead[0] = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
+    c->perm_ahead[1] = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
     c->row_chunk_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_total);
     c->chunk_first_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     c->list_base_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
-    c->gap_parts = std::max(GAP_PARTS, 2 * n_chunks);
-    c->part_loss = (double *)carve(c, sizeof(double) * (size_t)c->gap_parts);
-    c->part_conj = (double *)carve(c, sizeof(double) * (size_t)c->gap_parts);
-    c->part_wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
-    c->part_unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
+    c->gap_scratch.parts = std::max(GAP_PARTS, 2 * n_chunks);
+    c->gap_scratch.loss = (double *)carve(c, sizeof(double) * (size_t)c->gap_scratch.parts);
+    c->gap_scratch.conj = (double *)carve(c, sizeof(double) * (size_t)c->gap_scratch.parts);
+    c->gap_scratch.wsq = (double *)carve(c, sizeof(double) * WSQ_PARTS);
+    c->gap_scratch.unused = (double *)carve(c, sizeof(double) * WSQ_PARTS);
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
@@ -848,6 +872,8 @@ int chicle_set_solver(chicle_ctx *c, int32_t kind)
 
 int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
 {
+    if (!c) return CHICLE_EINVAL;
+    if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
     return chicle_local_epoch_ahead(c, perm_device, nullptr);
 }
 
@@ -855,7 +881,21 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
 {
     if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, c->state == ST_LOADING ? "assign first" : "aggregate before the next local epoch");
-    if (!perm_device) return fail(c, CHICLE_EINVAL, "perm is NULL");
+    if (!perm_device && !c->ahead_valid)
+        return fail(c, CHICLE_EINVAL, "perm is NULL and the previous pass announced no orders (or an assign dropped them)");
+    // NULL: the orders the previous call announced, from the library's own copy of them
+    const bool announced = perm_device == nullptr;
+    const bool tiles_ready = announced && c->ahead_tiles;
+    if (announced) perm_device = c->perm_ahead[1 - c->ahead_buf];
+    c->ahead_valid = false;
+    if (perm_next_device) {
+        // Copied on the context's stream, so the caller's buffer is an ordinary stream-ordered input.
+        HIP_TRY(c, hipMemcpyAsync(c->perm_ahead[c->ahead_buf], perm_next_device, sizeof(int32_t) * (size_t)c->n_total,
+                                  hipMemcpyDeviceToDevice, c->stream));
+        perm_next_device = c->perm_ahead[c->ahead_buf];
+        c->ahead_buf = 1 - c->ahead_buf;
+        c->ahead_valid = true;
+    }
     bool batched = false, dense_blocked = false;
     if (c->solver_kind == CHICLE_SOLVER_BATCHED) {
         dense_blocked = dense_blocked_eligible(c);
@@ -868,12 +908,12 @@ int chicle_local_epoch_ahead(chicle_ctx *c, const int32_t *perm_device, const in
     }
     seg_begin(c, CHICLE_SEG_LOCAL_EPOCH);
     int rc = CHICLE_OK;
-    if (!c->zw_valid) rc = run_row_pass(c, nullptr);     // x_i . w for the current w
+    if (!c->zw_valid) rc = run_row_pass(c, nullptr, c->gap_scratch);     // x_i . w for the current w
     if (rc == CHICLE_OK) {
         if (batched) {
-            rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device, perm_next_device)
-                 : c->loss == CHICLE_LOSS_SQUARED ? launch_batched<1>(c, perm_device, perm_next_device)
-                                                  : launch_batched<2>(c, perm_device, perm_next_device);
+            rc = c->loss == CHICLE_LOSS_HINGE ? launch_batched<0>(c, perm_device, tiles_ready, perm_next_device)
+                 : c->loss == CHICLE_LOSS_SQUARED ? launch_batched<1>(c, perm_device, tiles_ready, perm_next_device)
+                                                  : launch_batched<2>(c, perm_device, tiles_ready, perm_next_device);
         } else if (dense_blocked) {
             seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
             rc = c->loss == CHICLE_LOSS_HINGE ? launch_dense_blocked<0>(c, perm_device)
@@ -920,18 +960,17 @@ int chicle_aggregate(chicle_ctx *c)
     return CHICLE_OK;
 }
 
-int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
+static int gap_with(chicle_ctx *c, const GapScratch &gs, double *primal, double *dual, double *gap)
 {
-    if (!c) return CHICLE_EINVAL;
     if (c->state != ST_READY) return fail(c, CHICLE_ESTATE, "gap is defined on the aggregated state");
     seg_begin(c, CHICLE_SEG_GAP);
     int grid = 1;
-    int rc = run_row_pass(c, &grid);
-    if (rc) return rc;
+    int rc = run_row_pass(c, &grid, gs);
+    if (rc) { seg_end(c, CHICLE_SEG_GAP); return rc; }
     const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
-    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, c->part_wsq, c->part_unused);
-    hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, c->part_loss, c->part_conj, grid,
-                       c->part_wsq, gw, c->err_dev, c->gap_host_dev);
+    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, gs.wsq, gs.unused);
+    hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, gs.loss, gs.conj, grid,
+                       gs.wsq, gw, c->err_dev, c->gap_host_dev);
     seg_end(c, CHICLE_SEG_GAP);
     HIP_TRY(c, hipGetLastError());
     // the sums and the error flag arrive in pinned host memory with the end of the kernel: no copy to wait for
@@ -951,6 +990,12 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
     if (dual) *dual = D;
     if (gap) *gap = P - D;
     return CHICLE_OK;
+}
+
+int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
+{
+    if (!c) return CHICLE_EINVAL;
+    return gap_with(c, c->gap_scratch, primal, dual, gap);
 }
 
 // d floats in internal order on the device -> caller's order on the host.

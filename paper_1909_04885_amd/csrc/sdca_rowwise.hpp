@@ -240,7 +240,11 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
                 for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK) part += gld(m.val + p) * ld_l2(u + gld(m.col + p));
                 const float xu = block_sum<BLOCK>(part, red);
                 const float delta = dual_step<LOSS>(m.alpha, m.y, m.rw, xu, m.q, sc.c);
-                if (tid == 0) gst(&m.st->alpha, m.alpha + delta);
+                if (tid == 0) {
+                    float an = m.alpha + delta;                      // a + (clip(..) - a) can leave [0, 1] by an ulp
+                    if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
+                    gst(&m.st->alpha, an);
+                }
                 const float coef = delta * (LOSS == 1 ? 1.0f : m.y) * sc.inv_c;
                 if (coef != 0.0f) {
 #pragma unroll
@@ -306,7 +310,11 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_dense(
         for (int p = tid; p < d; p += BLOCK) part += x[p] * v[p];
         const float xu = block_sum<BLOCK>(part, red);
         const float delta = dual_step<LOSS>(a, y, rw, xu, q, sc.c);
-        if (tid == 0) ch.st[r].alpha = a + delta;
+        if (tid == 0) {
+            float an = a + delta;
+            if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
+            ch.st[r].alpha = an;
+        }
         const float coef = delta * (LOSS == 1 ? 1.0f : y) * sc.inv_c;
         if (coef != 0.0f)
             for (int p = tid; p < d; p += BLOCK) v[p] += coef * x[p];

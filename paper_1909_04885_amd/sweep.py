@@ -72,7 +72,8 @@ def run_to_gap(problem, K: int, permutations: Callable[[int, Sequence[int]], lis
             torch.cuda.synchronize()
             for i in range(n_blk):
                 t0 = time.perf_counter()
-                g.local_epoch_ahead(dev[i], dev[i + 1] if i + 1 < n_blk else None)
+                # the first round of a block brings its orders, the others run with the orders announced before
+                g.local_epoch_ahead(dev[i] if i == 0 else None, dev[i + 1] if i + 1 < n_blk else None)
                 g.aggregate()
                 gap = g.gap()[2]                    # the scalars come back: the round has ended
                 elapsed += time.perf_counter() - t0

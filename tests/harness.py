@@ -13,6 +13,25 @@ from workloads.configs import k_for_round, speeds_for
 # duality gap.  fp32 kernels against the fp64 oracle, free-running (no resynchronisation).
 TOL_DW = 1e-4
 TOL_GAP = 1e-3
+# Both sides keep alpha and the shared vector's mirror in fp32 on the device.  Once a run has converged so far
+# that an update is smaller than the fp32 resolution of the vector it is added to, an error relative to the
+# update measures rounding of the state, not the update: the error of every Delta w is therefore taken
+# relative to max(|Delta w_ref|, DW_FLOOR_ULPS * 2^-23 * |w| / TOL_DW), i.e. it passes when it is within
+# 1e-4 of the update or within DW_FLOOR_ULPS units in the last place of |w|, whichever is larger.
+# Applied to every loss and every case.
+EPS32 = 2.0 ** -23
+DW_FLOOR_ULPS = 1.0
+
+
+def gap_tolerance(gap_ref: float, primal_ref: float) -> float:
+    """The final gap must be within 1e-3 of the oracle's, or within one unit in the last place (fp32, the
+    precision of the state) of the primal value it is the difference of, whichever is larger: a gap far
+    below 2^-23 |P| is below what fp32 alpha and w can express."""
+    return max(TOL_GAP * abs(gap_ref), EPS32 * abs(primal_ref))
+
+
+def dw_floor(wnorm: float) -> float:
+    return max(DW_FLOOR_ULPS * EPS32 * wnorm / TOL_DW, 1e-12 * max(wnorm, 1.0))
 
 
 @functools.lru_cache(maxsize=2)
@@ -41,7 +60,10 @@ def greedy_tables(cfg, p, oracle_mod, binding_mod):
 
 def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sample_solvers=None,
                  check_alpha_every=0, log=None, ahead=False, tables=None, max_solvers=None):
-    """Returns a dict of per-round records; raises AssertionError on the first violation.
+    """`sample_solvers`: None compares every solver's Delta w in every round; a list compares every solver
+    in the first, the middle and the last round and those of the list in the others (the summed update is
+    compared in every round either way).  Returns a list of per-round records; raises AssertionError on the
+    first violation.
 
     `tables(r, K_prev, table_prev)` returns None (no change before round r) or (K, table from the
     oracle side, table from the library side); default: the configured greedy schedule."""
@@ -55,7 +77,7 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
     K = None
     rec = []
     loads = p.chunk_nnz()
-    next_dev = None      # visiting orders of round r already in HBM (announced during round r - 1)
+    announced = False    # the previous round announced this round's visiting orders
     for r in range(rounds):
         change = tables(r, K, table)
         if change is not None:
@@ -76,25 +98,30 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
         if not ahead:
             g.local_epoch(g.upload_perm(perms))
         else:
-            # announce the next round's orders unless the schedule reassigns chunks before it
-            cur_dev = next_dev if next_dev is not None else g.upload_perm(perms)
+            # announce the next round's orders unless the schedule reassigns chunks before it; a round whose
+            # orders were announced runs with the library's copy of them (the tensor is gone by then)
+            cur_dev = None if announced else g.upload_perm(perms)
             next_dev = None
             if r + 1 < rounds and tables(r + 1, K, table) is None:
                 next_dev = g.upload_perm(round_permutations(cfg["seed"], r + 1, o.rows_per_solver()))
             g.local_epoch_ahead(cur_dev, next_dev)
+            announced = next_dev is not None
+            del cur_dev, next_dev
         wnorm = float(np.linalg.norm(o.w))
         worst = [0.0]
-        which = set(range(K)) if sample_solvers is None else {s % K for s in sample_solvers}
+        every = sample_solvers is None or r in (0, rounds // 2, rounds - 1)
+        which = set(range(K)) if every else {s % K for s in sample_solvers}
+        floor = dw_floor(wnorm)
 
         def on_delta(k, dw):
             if k in which:
-                e = rel_l2(g.get_delta_w(k), dw, 1e-12 * max(wnorm, 1.0))
+                e = rel_l2(g.get_delta_w(k), dw, floor)
                 worst[0] = max(worst[0], e)
                 assert e <= TOL_DW, "round %d solver %d: Delta w rel L2 error %.3e" % (r, k, e)
 
         o.local_epoch(perms, keep_deltas=False, on_delta=on_delta)
         tot = o._pending
-        e_sum = rel_l2(g.get_delta_w(-1), tot, 1e-12 * max(wnorm, 1.0))
+        e_sum = rel_l2(g.get_delta_w(-1), tot, floor)
         assert e_sum <= TOL_DW, "round %d: summed Delta w rel L2 error %.3e" % (r, e_sum)
         o.aggregate()
         g.aggregate()
@@ -113,7 +140,7 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
                 a = g.get_alpha(c)
                 assert np.max(np.abs(a.astype(np.float64) - o.alpha[r0:r1])) <= 5e-4, "alpha drift in chunk %d" % c
     last = rec[-1]
-    assert abs(last["gap_gpu"] - last["gap_ref"]) <= TOL_GAP * abs(last["gap_ref"]), \
+    assert abs(last["gap_gpu"] - last["gap_ref"]) <= gap_tolerance(last["gap_ref"], last["P_ref"]), \
         "final gap %.9e vs %.9e" % (last["gap_gpu"], last["gap_ref"])
     g.close()
     return rec
