@@ -24,14 +24,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(p, table, K):
+def algorithmic_bytes(p, K, touched):
     """Bytes the local pass must move per launch: the matrix once, the per-row state once, and each
     solver's touched part of its private vector in and out once (cache traffic is not counted).
     CSR: 8 B per entry + 24 B per row (row offset, order entry, label, norm, alpha read and write)
-    + 8 B per distinct column a solver touches.  Dense: 4 B per entry + 20 B per row + 8 B per column
-    per solver."""
+    + 8 B per distinct column a solver touches (`touched`: their number over all solvers).  Dense:
+    4 B per entry + 20 B per row + 8 B per column per solver."""
     if p.dense:
         return 4 * p.nnz + 20 * p.n + 8 * p.d * K
+    return 8 * p.nnz + 24 * p.n + 8 * touched
+
+
+def aggregate_bytes(p, table, K, touched):
+    """Bytes the merge must move: every solver's update once in and (cleared) once out, w in and out in
+    double plus its float mirror out.  Where a private vector is mostly untouched (long-row workload)
+    only the touched columns count: 8 B per distinct column a solver touches + the shared vector."""
+    dense = 4 * p.d * (2 * K) + 20 * p.d
+    if touched is None:
+        return dense
+    return min(dense, 8 * touched + 20 * p.d)
+
+
+def touched_columns(p, table, K):
+    """Distinct (solver, column) pairs of the assignment (sparse workloads)."""
     touched = 0
     for k in range(K):
         seen = np.zeros(p.d, dtype=bool)
@@ -39,7 +54,38 @@ def algorithmic_bytes(p, table, K):
             r0, r1 = p.chunk_rows(c)
             seen[p.col[p.row_ptr[r0]:p.row_ptr[r1]]] = True
         touched += int(seen.sum())
-    return 8 * p.nnz + 24 * p.n + 8 * touched
+    return touched
+
+
+def stream_copy_gbs(torch, n_bytes=1 << 30, reps=5):
+    """What a plain device-to-device copy reaches on this GPU (bytes read + bytes written per second): the
+    practical ceiling to set beside the datasheet's 8 TB/s."""
+    src = torch.empty(n_bytes // 4, dtype=torch.float32, device="cuda:0").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = 0.0
+    for _ in range(reps):
+        e0.record()
+        dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2.0 * n_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
+
+
+def host_cpu():
+    model, total = "unknown", os.cpu_count()
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return model, total
 
 
 def cpu_baseline(p, cfg, table, K, budget_s=15.0):
@@ -58,7 +104,9 @@ def cpu_baseline(p, cfg, table, K, budget_s=15.0):
         o.gap()
         spent += time.perf_counter() - t0
         rounds += 1
+    model, total = host_cpu()
     return {"value": p.nnz * rounds / spent, "unit": "nnz/s", "cores": 1, "kind": "oracle",
+            "cpu_model": model, "host_cores_total": total,
             "sample": "%d whole rounds of the same workload (local pass + aggregate + gap), %.1f s" % (rounds, spent)}
 
 
@@ -77,6 +125,8 @@ def main():
     ap.add_argument("--gap-round-cap", type=int, default=100)
     ap.add_argument("--scale-in-from", type=int, default=0, metavar="K0",
                     help="also time the run to the gap target that starts with K0 solvers and scales in as rounds stall")
+    ap.add_argument("--repeats", type=int, default=3,
+                    help="timed runs of --steps rounds each; `value` is the first, the others are reported beside it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (untimed), as a reference for HBM byte counters")
     args = ap.parse_args()
@@ -105,7 +155,7 @@ def main():
     g.set_solver(args.solver)
     g.assign(K, table)
     rows = g.solver_rows()
-    total = args.warmup + args.steps
+    total = args.warmup + args.steps * max(args.repeats, 1)
     perms = [g.upload_perm(round_permutations(cfg["seed"], r, rows)) for r in range(total)]
     g.set_profiling(True)
     if args.calibrate_copy:
@@ -126,32 +176,41 @@ def main():
     for r in range(args.warmup):
         g.local_epoch_ahead(cur(r), nxt(r)); g.aggregate(); g.gap()
     torch.cuda.synchronize()
+    copy_gbs = stream_copy_gbs(torch)
     seg_ms = {"local_epoch": [], "aggregate": [], "gap": [], "epoch_gram": [], "epoch_chain": []}
     gaps = []
-    t_start = time.perf_counter()
-    for r in range(args.warmup, total):
-        g.local_epoch_ahead(cur(r), nxt(r))       # announces the next round's orders (all are in HBM)
-        g.aggregate()
-        gaps.append(g.gap()[2])          # synchronises: the three scalars come back to the host
-        for s in seg_ms:                  # events of this round have completed
-            try:
-                seg_ms[s].append(g.last_kernel_ms(s))
-            except chicle.ChicleError:
-                pass                      # segment not part of this solver kind
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
+    run_ms = []
+    r = args.warmup
+    for run in range(max(args.repeats, 1)):
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            g.local_epoch_ahead(cur(r), nxt(r))       # announces the next round's orders (all are in HBM)
+            g.aggregate()
+            gaps.append(g.gap()[2])          # synchronises: the three scalars come back to the host
+            for s in seg_ms:                  # events of this round have completed
+                try:
+                    seg_ms[s].append(g.last_kernel_ms(s))
+                except chicle.ChicleError:
+                    pass                      # segment not part of this solver kind
+            r += 1
+        torch.cuda.synchronize()
+        run_ms.append((time.perf_counter() - t_start) * 1e3 / args.steps)
+    ms_per_step = run_ms[0]                   # the K timed steps of the contract: the first run
 
-    ms_per_step = elapsed * 1e3 / args.steps
-    epoch_ms = float(np.mean(seg_ms["local_epoch"]))
-    agg_ms = float(np.mean(seg_ms["aggregate"]))
-    gap_ms = float(np.mean(seg_ms["gap"]))
-    abytes = algorithmic_bytes(p, table, K)
+    def med(name):
+        return float(np.median(seg_ms[name])) if seg_ms[name] else None
+
+    epoch_ms, agg_ms, gap_ms = med("local_epoch"), med("aggregate"), med("gap")
+    touched = None if p.dense else touched_columns(p, table, K)
+    abytes = algorithmic_bytes(p, K, touched)
     achieved = abytes / (epoch_ms * 1e-3) / 1e9
-    agg_bytes = 4 * p.d * (2 * K + 2)
+    agg_bytes = aggregate_bytes(p, table, K, touched)
     gap_bytes = (8 if not p.dense else 4) * p.nnz + 12 * p.n + 4 * p.d
+    traffic = stored_traffic("%s/%s" % (args.workload, args.size)) if args.solver == "auto" and not args.loss else None
     out = {
         "metric": "nnz_per_s_per_cocoa_round",
-        "value": p.nnz * args.steps / elapsed,
+        "value": p.nnz / (ms_per_step * 1e-3),
         "unit": "nnz/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -159,23 +218,33 @@ def main():
         "config": {"workload": "%s/%s" % (args.workload, args.size), "n": p.n, "d": p.d, "entries": p.nnz,
                    "K": K, "chunk_rows": cfg["chunk_rows"], "lambda": cfg["lam"], "loss": p.loss,
                    "solver": args.solver},
+        # every timed run of `steps` rounds; segment times below are medians over the rounds of all runs
+        "runs_ms_per_step": run_ms, "ms_per_step_median_of_runs": float(np.median(run_ms)),
+        # The local pass as the round sees it: everything chicle_local_epoch enqueues on the context's stream,
+        # the wait for the Gram tiles included.  chain_ms: the kernel that takes the coordinate steps;
+        # gram_ms: the Gram-tile kernel of the next pass, which runs beside it on the other compute units.
         "local_epoch": {"ms": epoch_ms, "nnz_per_s": p.nnz / (epoch_ms * 1e-3),
                         "coord_updates_per_s": p.n / (epoch_ms * 1e-3),
-                        "gram_ms": float(np.mean(seg_ms["epoch_gram"])) if seg_ms["epoch_gram"] else None,
-                        "chain_ms": float(np.mean(seg_ms["epoch_chain"])) if seg_ms["epoch_chain"] else None,
+                        "gram_ms": med("epoch_gram"), "chain_ms": med("epoch_chain"),
                         # the dependency chain: a solver's coordinate steps come one after the other
                         "max_rows_per_solver": int(max(rows)),
                         "ns_per_step_of_longest_solver": epoch_ms * 1e6 / max(int(max(rows)), 1)},
-        "aggregate": {"ms": agg_ms, "GB_per_s": agg_bytes / (agg_ms * 1e-3) / 1e9,
+        "aggregate": {"ms": agg_ms, "algorithmic_bytes": agg_bytes, "GB_per_s": agg_bytes / (agg_ms * 1e-3) / 1e9,
                       "frac_hbm_peak": agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "gap": {"ms": gap_ms, "GB_per_s": gap_bytes / (gap_ms * 1e-3) / 1e9,
+        "gap": {"ms": gap_ms, "algorithmic_bytes": gap_bytes, "GB_per_s": gap_bytes / (gap_ms * 1e-3) / 1e9,
                 "frac_hbm_peak": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "first": gaps[0], "last": gaps[-1]},
         "roofline": {"kernel": "local_epoch", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     # measured HBM bytes per launch of the chain kernel; null unless they were taken on
-                     # exactly these kernel sources (paper_1909_04885_amd/record_traffic.py)
-                     "traffic": stored_traffic("%s/%s" % (args.workload, args.size)) if args.solver == "auto" else None,
+                     # what a plain device copy reaches on this GPU, and the fraction of that
+                     "stream_copy_GBps": copy_gbs, "frac_of_stream_copy": achieved / copy_gbs,
+                     # Bytes that left L2 per round for the local pass (chain kernel + Gram kernel), from
+                     # FETCH_SIZE / WRITE_SIZE counter runs scaled by a plain copy of known size; null unless
+                     # taken on exactly these kernel sources.  Infinity-Cache hits are included: the counters
+                     # sit between L2 and the fabric, not at the HBM pins.
+                     "traffic": None if traffic is None else traffic["local_pass_bytes"],
+                     "traffic_by_kernel": None if traffic is None else traffic["kernels"],
+                     "traffic_unit": "bytes between L2 and the fabric per round",
                      "algorithmic_bytes": abytes},
     }
     g.close()
