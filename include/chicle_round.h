@@ -231,6 +231,16 @@ int chicle_aggregate(chicle_ctx *ctx);
  * Errors: ESTATE, EDEVICE. */
 int chicle_gap(chicle_ctx *ctx, double *primal, double *dual, double *gap);
 
+/* chicle_gap for callers that cannot allocate device memory or hand over a workspace for this call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * kernels and same results as chicle_gap; the kernels' partial sums go to a fixed array in the library's
+ * code object (136 KB, one copy per GPU, held until the process ends) instead of the arena.  The call
+ * allocates nothing.  Limit: at most 4096 chunks (EINVAL beyond).  All contexts on one GPU share that
+ * array: every call overwrites what it reads later, so nothing needs clearing, but two such calls that
+ * overlap in time on one GPU (different streams or threads) race.  Errors as chicle_gap, plus EINVAL for
+ * the limit and EDEVICE when the array's address could not be obtained at chicle_create. */
+int chicle_gap_noalloc(chicle_ctx *ctx, double *primal, double *dual, double *gap);
+
 /* State access: the shared vector, and the per-sample state that lives inside its chunk and moves with it
  * (Section 4.4 "In-memory chunk data format"); what a trainer checkpoints or restores between iterations.
  * Host arrays of d floats / n_rows-of-that-chunk floats.  get_* synchronise.

@@ -29,7 +29,7 @@ EXPORTS = [
     "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
     "chicle_solver_ms", "chicle_projected_iteration_time", "chicle_scale_out", "chicle_scale_in",
-    "chicle_rebalance", "chicle_next_solver_count",
+    "chicle_rebalance", "chicle_next_solver_count", "chicle_gap_noalloc",
 ]
 
 
@@ -72,6 +72,7 @@ def load_library():
         "chicle_local_epoch_host_perm": (ctypes.c_int, [vp, vp]),
         "chicle_aggregate": (ctypes.c_int, [vp]),
         "chicle_gap": (ctypes.c_int, [vp, ctypes.POINTER(dbl), ctypes.POINTER(dbl), ctypes.POINTER(dbl)]),
+        "chicle_gap_noalloc": (ctypes.c_int, [vp, ctypes.POINTER(dbl), ctypes.POINTER(dbl), ctypes.POINTER(dbl)]),
         "chicle_get_w": (ctypes.c_int, [vp, vp]),
         "chicle_set_w": (ctypes.c_int, [vp, vp]),
         "chicle_get_delta_w": (ctypes.c_int, [vp, i32, vp]),
@@ -310,6 +311,11 @@ class ChicleRound:
     def gap(self):
         p, dd, g = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
         self._check(self._L.chicle_gap(self._h, ctypes.byref(p), ctypes.byref(dd), ctypes.byref(g)))
+        return p.value, dd.value, g.value
+
+    def gap_noalloc(self):
+        p, dd, g = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        self._check(self._L.chicle_gap_noalloc(self._h, ctypes.byref(p), ctypes.byref(dd), ctypes.byref(g)))
         return p.value, dd.value, g.value
 
     # -- state access

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <string>
@@ -51,6 +52,41 @@ struct GapScratch {
     double *loss = nullptr, *conj = nullptr, *wsq = nullptr, *unused = nullptr;
     int parts = 0;            // length of loss[] and conj[]
 };
+
+// Scratch of chicle_gap_noalloc: a fixed array in the code object, one copy per GPU, kept until the process
+// ends.  Layout: GAP_PARTS loss partials, GAP_PARTS conjugate partials, 2 * WSQ_PARTS for |w|^2.
+constexpr int STATIC_SCRATCH_DOUBLES = 2 * GAP_PARTS + 2 * WSQ_PARTS;
+constexpr int MAX_DEVICES = 64;
+
+}  // namespace
+
+static __device__ __align__(256) double scratch[STATIC_SCRATCH_DOUBLES];
+
+namespace {
+
+// Device address of `scratch` on the current device (in host code the array's name is not one), looked
+// up once per device.
+double *scratch_ptr[MAX_DEVICES];
+bool scratch_known[MAX_DEVICES];
+std::mutex scratch_mutex;
+
+hipError_t static_scratch_of_current_device(double **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_known[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        scratch_ptr[dev] = (double *)p;
+        scratch_known[dev] = true;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -98,6 +134,7 @@ struct chicle_ctx {
     bool zw_valid = true;      // the rows' residuals match w (set at load time for w = 0)
     int32_t *perm_stage = nullptr;
     GapScratch gap_scratch;           // in the arena
+    double *static_scratch = nullptr; // this device's copy of the fixed scratch array (chicle_gap_noalloc)
     double *gap_host = nullptr;       // 4 doubles of pinned host memory the gap's last kernel writes into ...
     double *gap_host_dev = nullptr;   // ... through this device address
     int *err_dev = nullptr;
@@ -608,6 +645,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->gap_host, sizeof(double) * 4, hipHostMallocMapped) == hipSuccess &&
          hipHostGetDevicePointer((void **)&c->gap_host_dev, c->gap_host, 0) == hipSuccess;
+    ok = ok && static_scratch_of_current_device(&c->static_scratch) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
          hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
          hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
@@ -996,6 +1034,21 @@ int chicle_gap(chicle_ctx *c, double *primal, double *dual, double *gap)
 {
     if (!c) return CHICLE_EINVAL;
     return gap_with(c, c->gap_scratch, primal, dual, gap);
+}
+
+int chicle_gap_noalloc(chicle_ctx *c, double *primal, double *dual, double *gap)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (2 * (int64_t)c->n_chunks > GAP_PARTS)
+        return fail(c, CHICLE_EINVAL, "%d chunks: the fixed scratch holds partial sums for at most %d", c->n_chunks, GAP_PARTS / 2);
+    if (!c->static_scratch) return fail(c, CHICLE_EDEVICE, "the fixed scratch array was not found on this device");
+    GapScratch gs;
+    gs.loss = c->static_scratch;
+    gs.conj = gs.loss + GAP_PARTS;
+    gs.wsq = gs.conj + GAP_PARTS;
+    gs.unused = gs.wsq + WSQ_PARTS;
+    gs.parts = GAP_PARTS;
+    return gap_with(c, gs, primal, dual, gap);
 }
 
 // d floats in internal order on the device -> caller's order on the host.
