@@ -119,12 +119,13 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_stored_traffic_is_tied_to_the_kernel_sources(tmp_path, monkeypatch):
     from paper_1909_04885_amd import record_traffic as rt
-    rec = {"workload": "w/full", "hbm_bytes_per_launch": 5.0, "source_sha256": rt.source_hash()}
+    rec = {"workload": "w/full", "kernels": {"a": 2.0, "b": 3.0}, "local_pass_bytes": 5.0,
+           "source_sha256": rt.source_hash()}
     f = tmp_path / "t.json"
     monkeypatch.setattr(rt, "TRAFFIC_FILE", str(f))
     assert rt.stored_traffic("w/full") is None                 # no record
     f.write_text(__import__("json").dumps(rec))
-    assert rt.stored_traffic("w/full") == 5.0
+    assert rt.stored_traffic("w/full") == {"kernels": {"a": 2.0, "b": 3.0}, "local_pass_bytes": 5.0}
     assert rt.stored_traffic("other/full") is None
     rec["source_sha256"] = "0" * 64                             # measured on other sources
     f.write_text(__import__("json").dumps(rec))
