@@ -60,7 +60,8 @@ enum chicle_status {
     CHICLE_EINVAL = -1,   /* bad argument, malformed chunk, bad table */
     CHICLE_ENOMEM = -2,   /* arena too small */
     CHICLE_ESTATE = -3,   /* call not legal in the current state (ownership contract) */
-    CHICLE_EDEVICE = -4   /* HIP error, or a kernel flagged bad input (e.g. perm entry out of range) */
+    CHICLE_EDEVICE = -4   /* HIP error, or a kernel flagged bad input (e.g. perm entry out of range) or gave
+                             up a bounded wait between the workgroups that share a solver */
 };
 
 enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1, CHICLE_LOSS_LOGISTIC = 2 };
@@ -69,10 +70,14 @@ enum chicle_loss { CHICLE_LOSS_HINGE = 0, CHICLE_LOSS_SQUARED = 1, CHICLE_LOSS_L
  * given order; they differ only in floating-point summation order). */
 enum chicle_solver_kind {
     CHICLE_SOLVER_AUTO = 0,       /* choose from the data shape */
-    CHICLE_SOLVER_ROWWISE = 1,    /* one coordinate step at a time */
-    CHICLE_SOLVER_BATCHED = 2     /* blocks of 64 rows via their Gram matrix, same sequence of steps: sparse rows
+    CHICLE_SOLVER_ROWWISE = 1,    /* one coordinate step at a time; where sparse rows are long (more than 96 entries
+                                     on average) and the chip has more compute units than solvers, several
+                                     workgroups share every solver, each owning a range of columns (Section 4.2:
+                                     a solver may use all processors of its node) */
+    CHICLE_SOLVER_BATCHED = 2,    /* blocks of 64 rows via their Gram matrix, same sequence of steps: sparse rows
                                      of at most 48 entries (dense rows that short are stored that way), or dense
                                      rows of at most 320 columns; else EINVAL at the pass */
+    CHICLE_SOLVER_ROWWISE_ONE_CU = 3  /* row-wise with every solver on one compute unit */
 };
 
 /* Timed segments reported by chicle_last_kernel_ms. */

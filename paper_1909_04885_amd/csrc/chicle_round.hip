@@ -22,6 +22,7 @@
 #include "sdca_batched.hpp"
 #include "sdca_batched_dense.hpp"
 #include "sdca_rowwise.hpp"
+#include "sdca_rowwise_cluster.hpp"
 
 using namespace chicle;
 
@@ -35,6 +36,7 @@ constexpr int DENSE_V_LDS_MAX_D = 8192;
 constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
 constexpr int ENTRY_SLACK = 64;        // readable entries past the last row of a chunk
+constexpr double LONG_ROW_AVG = 96.0;  // sparse rows longer than this on average: the row-wise solver uses whole workgroups per row
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
 
@@ -139,6 +141,14 @@ struct chicle_ctx {
     double *gap_host_dev = nullptr;   // ... through this device address
     int *err_dev = nullptr;
     int *progress_dev = nullptr;      // per solver: block its batched pass has reached
+    // long sparse rows: several workgroups (a cluster) share every solver of the row-wise pass
+    bool long_rows = false;           // average row longer than LONG_ROW_AVG
+    int32_t *row_split_dev = nullptr; // per row: where the columns of cluster members 1.. begin
+    unsigned long long *cluster_ring_dev = nullptr;
+    int cluster = 1;                  // members per solver under the current assignment
+    int split_built_for = 0;          // cluster size row_split_dev was built for
+    bool cluster_allowed = true;
+    int cu_count = 0;                 // compute units of the device
     long long *ticks_dev = nullptr;   // 2 per solver: clock at start / end of its last pass
     int wall_khz = 0;                 // rate of that clock
     bool epoch_ran = false;
@@ -190,7 +200,7 @@ void *carve(chicle_ctx *c, size_t bytes)
     return p;
 }
 
-size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers)
+size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows)
 {
     const int64_t ld = pad_d(d);
     size_t s = 0;
@@ -210,6 +220,10 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(int));
     s += align_up(sizeof(long long) * 2 * (size_t)max_solvers);
     s += align_up(sizeof(int) * (size_t)max_solvers);
+    if (long_rows) {
+        s += align_up(sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
+        s += align_up(sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+    }
     return s;
 }
 
@@ -246,6 +260,8 @@ int check_deferred(chicle_ctx *c)
         HIP_TRY(c, hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream));
         if (flag & ERR_PERM_RANGE)
             return fail(c, CHICLE_EDEVICE, "a visiting-order entry was outside [0, rows of its solver)");
+        if (flag & ERR_PARTNER_TIMEOUT)
+            return fail(c, CHICLE_EDEVICE, "the workgroups that share a solver lost each other; the pass is invalid");
         return fail(c, CHICLE_EDEVICE, "kernel error flag %d", flag);
     }
     return CHICLE_OK;
@@ -332,7 +348,15 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
         const double avg = c->n_total ? (double)c->total_entries / (double)c->n_total : 0.0;
         const int ml = std::max(c->max_list, 1);
         const size_t sh = (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml;
-        if (avg <= 96.0)
+        if (c->long_rows && c->cluster > 1 && c->cluster_allowed) {
+            // every solver shared by a cluster of workgroups on one L2 partition, each owning a range of columns
+            const int k_pad = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
+            HIP_TRY(c, hipMemsetAsync(c->cluster_ring_dev, 0, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)c->K, c->stream));
+            hipLaunchKernelGGL((sdca_rowwise_csr_cluster<LOSS, 256, 2>), dim3(k_pad * c->cluster), dim3(256), sh, c->stream,
+                               c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev, k_pad, c->cluster, c->row_split_dev,
+                               c->cluster_ring_dev);
+        } else if (avg <= LONG_ROW_AVG)
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64, 2>), dim3(c->K), dim3(64), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
                                perm, c->u, c->ld_v, ml, sc, c->err_dev);
@@ -561,7 +585,8 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
                           int32_t max_solvers, int32_t dense)
 {
     if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
-    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers);
+    const bool long_rows = !dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
+    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers, long_rows);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
     const size_t per_chunk_slack = 8 * ALIGN + 2 * sizeof(float) * ENTRY_SLACK;
     if (dense && !dense_as_csr(d))
@@ -625,7 +650,12 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
-    if (!c->err_dev || !c->ticks_dev || !c->progress_dev) { delete c; return CHICLE_ENOMEM; }
+    c->long_rows = !c->api_dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
+    if (c->long_rows) {
+        c->row_split_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
+        c->cluster_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+    }
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || (c->long_rows && !c->cluster_ring_dev)) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -639,7 +669,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     {
         int dev = 0;
         ok = ok && hipGetDevice(&dev) == hipSuccess &&
-             hipDeviceGetAttribute(&c->wall_khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && c->wall_khz > 0;
+             hipDeviceGetAttribute(&c->wall_khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && c->wall_khz > 0 &&
+             hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && c->cu_count > 0;
     }
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
@@ -745,7 +776,7 @@ static int load_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32
         longest = std::max(longest, row_ptr[r + 1] - row_ptr[r]);
     }
     ChunkDev ch{};
-    ch.n_rows = n_rows; ch.nnz = nnz;
+    ch.n_rows = n_rows; ch.nnz = nnz; ch.row_base = (int32_t)c->rows_loaded;
     int32_t *rp = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(n_rows + 1));
     // a few entries of slack: kernels read short rows with fixed-width vector loads
     int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
@@ -791,7 +822,7 @@ int chicle_load_chunk_dense(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, con
         q[r] = (float)s;
     }
     ChunkDev ch{};
-    ch.n_rows = n_rows; ch.nnz = entries;
+    ch.n_rows = n_rows; ch.nnz = entries; ch.row_base = (int32_t)c->rows_loaded;
     float *xd = (float *)carve(c, sizeof(float) * (size_t)entries);
     if (!xd) return fail(c, CHICLE_ENOMEM, "chunk store full");
     ch.val = xd;
@@ -888,6 +919,20 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     c->n_tiles = tile;
     c->gap_items = items[c->n_chunks];
     c->state = ST_READY;
+    c->cluster = 1;
+    if (c->long_rows) {
+        // as many workgroups per solver as the chip has compute units for, each owning a range of columns
+        const int k_pad = (K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
+        c->cluster = std::max(1, std::min(CLUSTER_MAX, c->cu_count / k_pad));
+        if (c->cluster > 1 && c->split_built_for != c->cluster) {
+            int max_rows = 1;
+            for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
+            hipLaunchKernelGGL(row_split_offsets, dim3(grid_for(max_rows, 256, 64), c->n_chunks), dim3(256), 0, c->stream,
+                               c->chunks_dev, (int)c->d, c->cluster, c->row_split_dev);
+            HIP_TRY(c, hipGetLastError());
+            c->split_built_for = c->cluster;
+        }
+    }
     return clear_all_private(c);
 }
 
@@ -902,9 +947,11 @@ int chicle_solver_rows(chicle_ctx *c, int64_t *rows_out)
 int chicle_set_solver(chicle_ctx *c, int32_t kind)
 {
     if (!c) return CHICLE_EINVAL;
-    if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE && kind != CHICLE_SOLVER_BATCHED)
+    if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE && kind != CHICLE_SOLVER_BATCHED &&
+        kind != CHICLE_SOLVER_ROWWISE_ONE_CU)
         return fail(c, CHICLE_EINVAL, "unknown solver kind %d", kind);
-    c->solver_kind = kind;
+    c->cluster_allowed = kind != CHICLE_SOLVER_ROWWISE_ONE_CU;
+    c->solver_kind = kind == CHICLE_SOLVER_ROWWISE_ONE_CU ? CHICLE_SOLVER_ROWWISE : kind;
     return CHICLE_OK;
 }
 
@@ -1019,6 +1066,8 @@ static int gap_with(chicle_ctx *c, const GapScratch &gs, double *primal, double 
         HIP_TRY(c, hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream));
         if (flag & ERR_PERM_RANGE)
             return fail(c, CHICLE_EDEVICE, "a visiting-order entry was outside [0, rows of its solver)");
+        if (flag & ERR_PARTNER_TIMEOUT)
+            return fail(c, CHICLE_EDEVICE, "the workgroups that share a solver lost each other; the pass is invalid");
         return fail(c, CHICLE_EDEVICE, "kernel error flag %d", flag);
     }
     const double n = (double)c->n_total;

@@ -22,7 +22,7 @@ struct ChunkDev {
     const float *val;         // CSR values, or dense row-major n_rows x d
     RowState *st;             // per-row state, one 16-byte record per row
     int32_t n_rows;
-    int32_t pad_;
+    int32_t row_base;         // index of the chunk's first row in context-wide per-row tables
     int64_t nnz;              // stored entries
 };
 
@@ -53,5 +53,6 @@ __device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int solver,
 __device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int which) { stamp_solver(sc, blockIdx.x, which); }
 
 constexpr int ERR_PERM_RANGE = 1;
+constexpr int ERR_PARTNER_TIMEOUT = 2;   // the workgroups that share a solver lost each other
 
 }  // namespace chicle

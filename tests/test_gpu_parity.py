@@ -31,7 +31,9 @@ MINI_CASES = [("dense_hinge", "rowwise", False), ("dense_ridge", "rowwise", Fals
               ("sparse_zipf", "rowwise", False), ("sparse_longrow", "rowwise", False),
               ("elastic", "rowwise", False), ("sparse_zipf", "batched", False),
               ("elastic", "batched", False), ("sparse_zipf", "batched", True), ("elastic", "batched", True),
-              ("dense_ridge", "auto", True), ("dense_hinge", "auto", False), ("dense_hinge", "batched", False)]
+              ("dense_ridge", "auto", True), ("dense_hinge", "auto", False), ("dense_hinge", "batched", False),
+              # long rows with every solver kept on one compute unit ("rowwise" spreads it over several there)
+              ("sparse_longrow", "rowwise_one_cu", False)]
 
 
 @pytest.mark.parametrize("name,solver,ahead", MINI_CASES)
