@@ -57,6 +57,84 @@ __global__ __launch_bounds__(256) void delta_w_out(const float *u_all, int64_t l
     }
 }
 
+// The merge where private vectors are stored compactly (see layout.hpp).  A workgroup takes 256 consecutive
+// words of 32 columns (8192 columns) and walks the solvers: a solver's entries for these columns are one
+// contiguous run of its compact vector, which the workgroup reads (and clears) with coalesced accesses into
+// LDS; each thread then picks the entries of its own word out of the run, in order, by the word's bits.
+// u_off[k]: where solver k's compact vector starts in u.  Reads and clears only what the solvers touched.
+constexpr int AGG_WORDS = 256;                       // words (threads) per workgroup
+__global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, float *w32, float *u, const int64_t *__restrict__ u_off,
+                                                               const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
+                                                               int64_t words, int64_t d, int K, float inv_sigma)
+{
+    __shared__ float run[AGG_WORDS * 33];            // a run is at most all columns of the workgroup (32 per word;
+                                                     // 33: the sums are laid out one word per padded row at the end)
+    __shared__ unsigned touched[AGG_WORDS];
+    __shared__ int run_begin, run_end;
+    const int tid = threadIdx.x;
+    const int64_t j = (int64_t)blockIdx.x * AGG_WORDS + tid;
+    const bool live = j < words;
+    const int last = (int)min((int64_t)AGG_WORDS, words - (int64_t)blockIdx.x * AGG_WORDS) - 1;   // last live thread
+    float acc[32];
+#pragma unroll
+    for (int b = 0; b < 32; ++b) acc[b] = 0.f;
+    unsigned any = 0;
+    // (the next solver's word and prefix are requested before this solver's run is waited for)
+    unsigned m_next = live && K > 0 ? bits[j] : 0u;
+    int pf_next = live && K > 0 ? pref[j] : 0;
+    for (int k = 0; k < K; ++k) {
+        const unsigned m = m_next;
+        const int pf = pf_next;
+        if (k + 1 < K && live) { m_next = bits[(int64_t)(k + 1) * words + j]; pf_next = pref[(int64_t)(k + 1) * words + j]; }
+        if (tid == 0) run_begin = pf;
+        if (tid == last) run_end = pf + __popc(m);
+        __syncthreads();
+        const int begin = run_begin, len = run_end - begin;
+        float *uk = u + u_off[k] + begin;
+        for (int i = tid; i < len; i += AGG_WORDS) { run[i] = uk[i]; uk[i] = 0.f; }
+        __syncthreads();
+        any |= m;
+        int r = pf - begin;
+#pragma unroll
+        for (int b = 0; b < 32; ++b)
+            if (m & (1u << b)) acc[b] += run[r++];
+        __syncthreads();                             // the run is overwritten by the next solver's
+    }
+    // the sums go through LDS so that the shared vector is updated with coalesced accesses
+    touched[tid] = any;
+#pragma unroll
+    for (int b = 0; b < 32; ++b) run[tid * 33 + b] = acc[b];
+    __syncthreads();
+    const int64_t c0 = (int64_t)blockIdx.x * AGG_WORDS * 32;
+    for (int i = tid; i < AGG_WORDS * 32; i += AGG_WORDS) {
+        const int64_t c = c0 + i;
+        if (c < d && (touched[i >> 5] & (1u << (i & 31)))) {
+            const double x = w64[c] + (double)(run[(i >> 5) * 33 + (i & 31)] * inv_sigma);
+            w64[c] = x;
+            w32[c] = (float)x;
+        }
+    }
+}
+
+// Read-back helper for compact private vectors: out <- Delta w_solver, or sum_k Delta w_k when solver < 0.
+__global__ __launch_bounds__(256) void delta_w_out_compact(const float *u, const int64_t *__restrict__ u_off,
+                                                           const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
+                                                           int64_t words, int64_t d, int K, int solver, float inv_sigma,
+                                                           float *out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < d; c += stride) {
+        float acc = 0.f;
+        const int64_t j = c >> 5;
+        const unsigned bit = 1u << (c & 31);
+        for (int k = solver >= 0 ? solver : 0; k < (solver >= 0 ? solver + 1 : K); ++k) {
+            const unsigned m = bits[(int64_t)k * words + j];
+            if (m & bit) acc += u[u_off[k] + pref[(int64_t)k * words + j] + __popc(m & (bit - 1u))];
+        }
+        out[c] = acc * inv_sigma;
+    }
+}
+
 __device__ __forceinline__ double wave_sum_d(double x)
 {
 #pragma unroll

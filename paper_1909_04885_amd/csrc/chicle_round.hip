@@ -35,7 +35,6 @@ constexpr int MAX_LIST_LDS = 768;      // chunks one solver may own (their descr
 constexpr int DENSE_V_LDS_MAX_D = 8192;
 constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
-constexpr int ENTRY_SLACK = 64;        // readable entries past the last row of a chunk
 constexpr double LONG_ROW_AVG = 96.0;  // sparse rows longer than this on average: the row-wise solver uses whole workgroups per row
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
@@ -148,6 +147,15 @@ struct chicle_ctx {
     int cluster = 1;                  // members per solver under the current assignment
     int split_built_for = 0;          // cluster size row_split_dev was built for
     bool cluster_allowed = true;
+    // ... and private vectors are stored compactly (a solver touches a small part of the columns)
+    int64_t words = 0;                // 32-column words per bitmap
+    unsigned *bits_dev = nullptr;     // max_solvers x words: columns a solver's chunks contain
+    int32_t *pref_dev = nullptr;      // max_solvers x words: set bits before each word
+    int32_t *count_dev = nullptr;     // max_solvers: columns per solver
+    int64_t *u_off_dev = nullptr;     // max_solvers: start of each solver's compact vector in u
+    int32_t *chunk_owner_dev = nullptr;
+    int64_t u_capacity = 0;           // floats in u
+    int64_t u_used = 0;               // floats of u in use under the current assignment (compact storage)
     int cu_count = 0;                 // compute units of the device
     long long *ticks_dev = nullptr;   // 2 per solver: clock at start / end of its last pass
     int wall_khz = 0;                 // rate of that clock
@@ -200,7 +208,16 @@ void *carve(chicle_ctx *c, size_t bytes)
     return p;
 }
 
-size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows)
+// Floats of private-vector storage: dense, one vector per solver; compact (long rows): a solver's vector
+// holds only the columns its chunks contain, so all of them together hold at most one float per entry.
+int64_t private_floats(int64_t total_entries, int64_t ld, int32_t max_solvers, bool long_rows)
+{
+    const int64_t dense = ld * (int64_t)max_solvers;
+    return long_rows ? std::min(dense, total_entries + 64 * (int64_t)max_solvers) : dense;
+}
+
+size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows,
+                   int64_t n_total_entries_hint)
 {
     const int64_t ld = pad_d(d);
     size_t s = 0;
@@ -210,7 +227,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(int32_t) * ((size_t)n_chunks + 1));
     s += align_up(sizeof(float) * (size_t)ld) * 3;                       // w, tmp_a, tmp_b
     s += align_up(sizeof(double) * (size_t)ld);                          // w in double
-    s += align_up(sizeof(float) * (size_t)ld * (size_t)max_solvers);     // private vectors
+    s += align_up(sizeof(float) * (size_t)private_floats(n_total_entries_hint, ld, max_solvers, long_rows));   // private vectors
     s += 2 * align_up(sizeof(int32_t) * (size_t)d);                      // renumbering tables
     s += 2 * align_up(sizeof(float) * (size_t)TILE_FLOATS * (size_t)tiles_cap(n_total, max_solvers));
     s += align_up(sizeof(int32_t) * (size_t)tiles_cap(n_total, max_solvers));
@@ -223,16 +240,20 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     if (long_rows) {
         s += align_up(sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         s += align_up(sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+        const size_t words = ((size_t)d + 31) / 32;
+        s += 2 * align_up(sizeof(int32_t) * words * (size_t)max_solvers);          // column bitmaps, prefix counts
+        s += align_up(sizeof(int32_t) * (size_t)max_solvers) + align_up(sizeof(int64_t) * (size_t)max_solvers);
+        s += align_up(sizeof(int32_t) * (size_t)n_chunks);
     }
     return s;
 }
 
-size_t chunk_bytes(bool dense, int64_t n_rows, int64_t entries)
+size_t chunk_bytes(bool dense, bool long_rows, int64_t n_rows, int64_t entries)
 {
     size_t s = 0;
     if (!dense) {
         s += align_up(sizeof(int32_t) * (size_t)(n_rows + 1));
-        s += align_up(sizeof(int32_t) * (size_t)(entries + ENTRY_SLACK));
+        s += align_up(sizeof(int32_t) * (size_t)(entries + ENTRY_SLACK)) * (long_rows ? 2 : 1);   // column ids (+ compact ids)
     }
     s += align_up(sizeof(float) * (size_t)(entries + ENTRY_SLACK));
     s += align_up(sizeof(RowState) * (size_t)n_rows);
@@ -278,6 +299,10 @@ int grid_for(int64_t items, int per_block, int cap)
 int clear_all_private(chicle_ctx *c)
 {
     if (c->K <= 0) return CHICLE_OK;
+    if (c->long_rows) {
+        HIP_TRY(c, hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->u_used, c->stream));
+        return CHICLE_OK;
+    }
     const int64_t d4 = c->ld_v / 4;
     hipLaunchKernelGGL(clear_private, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->u,
                        c->ld_v, d4, c->K);
@@ -355,15 +380,15 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
             hipLaunchKernelGGL((sdca_rowwise_csr_cluster<LOSS, 256, 2>), dim3(k_pad * c->cluster), dim3(256), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
                                perm, c->u, c->ld_v, ml, sc, c->err_dev, k_pad, c->cluster, c->row_split_dev,
-                               c->cluster_ring_dev);
+                               c->cluster_ring_dev, c->u_off_dev);
         } else if (avg <= LONG_ROW_AVG)
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64, 2>), dim3(c->K), dim3(64), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->u, c->ld_v, ml, sc, c->err_dev);
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev, (const int64_t *)nullptr);
         else
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 512, 4>), dim3(c->K), dim3(512), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->u, c->ld_v, ml, sc, c->err_dev);
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev, (const int64_t *)c->u_off_dev);
     }
     HIP_TRY(c, hipGetLastError());
     return CHICLE_OK;
@@ -586,15 +611,15 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
 {
     if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
     const bool long_rows = !dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
-    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers, long_rows);
+    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers, long_rows, total_entries);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
     const size_t per_chunk_slack = 8 * ALIGN + 2 * sizeof(float) * ENTRY_SLACK;
     if (dense && !dense_as_csr(d))
         s += sizeof(float) * (size_t)total_entries + 4 * sizeof(float) * (size_t)n_total;
     else
-        s += (sizeof(int32_t) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
+        s += (sizeof(int32_t) * (long_rows ? 2 : 1) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
              sizeof(int32_t) * ((size_t)n_total + (size_t)n_chunks) + 4 * sizeof(float) * (size_t)n_total;
-    s += per_chunk_slack * (size_t)n_chunks;
+    s += (per_chunk_slack + (long_rows ? ALIGN + sizeof(int32_t) * ENTRY_SLACK : 0)) * (size_t)n_chunks;
     return s + ALIGN;
 }
 
@@ -630,7 +655,9 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->w64 = (double *)carve(c, sizeof(double) * (size_t)c->ld_v);
     c->tmp_a = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
     c->tmp_b = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
-    c->u = (float *)carve(c, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers);
+    c->long_rows = !c->api_dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
+    c->u_capacity = private_floats(total_entries, c->ld_v, max_solvers, c->long_rows);
+    c->u = (float *)carve(c, sizeof(float) * (size_t)c->u_capacity);
     c->rank_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
     c->col_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
     c->tiles[0] = (float *)carve(c, sizeof(float) * (size_t)TILE_FLOATS * (size_t)c->max_tiles);
@@ -650,12 +677,17 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
-    c->long_rows = !c->api_dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
     if (c->long_rows) {
         c->row_split_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         c->cluster_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+        c->words = ((int64_t)d + 31) / 32;
+        c->bits_dev = (unsigned *)carve(c, sizeof(unsigned) * (size_t)c->words * (size_t)max_solvers);
+        c->pref_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->words * (size_t)max_solvers);
+        c->count_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)max_solvers);
+        c->u_off_dev = (int64_t *)carve(c, sizeof(int64_t) * (size_t)max_solvers);
+        c->chunk_owner_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     }
-    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || (c->long_rows && !c->cluster_ring_dev)) { delete c; return CHICLE_ENOMEM; }
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || (c->long_rows && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -663,7 +695,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
               hipMemsetAsync(c->w64, 0, sizeof(double) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->tmp_a, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->tmp_b, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
-              hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->ld_v * (size_t)max_solvers, c->stream) == hipSuccess &&
+              hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->u_capacity, c->stream) == hipSuccess &&
               hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess &&
               hipMemsetAsync(c->ticks_dev, 0, sizeof(long long) * 2 * (size_t)max_solvers, c->stream) == hipSuccess;
     {
@@ -694,7 +726,7 @@ static int load_common(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, int64_t 
     if (c->rows_loaded + n_rows > c->n_total) return fail(c, CHICLE_EINVAL, "more rows than n_total");
     if (c->entries_loaded + entries > c->total_entries)
         return fail(c, CHICLE_EINVAL, "more stored entries than total_entries");
-    if (c->used + chunk_bytes(c->dense, n_rows, entries) > c->arena_bytes)
+    if (c->used + chunk_bytes(c->dense, c->long_rows, n_rows, entries) > c->arena_bytes)
         return fail(c, CHICLE_ENOMEM, "chunk store full");
     return CHICLE_OK;
 }
@@ -780,6 +812,10 @@ static int load_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32
     int32_t *rp = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(n_rows + 1));
     // a few entries of slack: kernels read short rows with fixed-width vector loads
     int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
+    if (c->long_rows) {      // compact ids, filled at every assign; must lie where chunk_compact_ids() looks
+        int32_t *ci = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
+        if (!ci || ci != cd + padded_entries(nnz)) return fail(c, CHICLE_ENOMEM, "chunk store full");
+    }
     float *vd = (float *)carve(c, sizeof(float) * (size_t)(nnz + ENTRY_SLACK));
     if (!vd) return fail(c, CHICLE_ENOMEM, "chunk store full");
     ch.row_ptr = rp; ch.col = cd; ch.val = vd;
@@ -921,6 +957,29 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     c->state = ST_READY;
     c->cluster = 1;
     if (c->long_rows) {
+        // Compact private vectors: which columns each solver's chunks contain, where each of them lives in
+        // the solver's vector, and that index for every stored entry.
+        int64_t max_nnz = 1;
+        for (const ChunkDev &ch : c->chunks) max_nnz = std::max(max_nnz, padded_entries(ch.nnz));
+        const dim3 egrid(grid_for(max_nnz, 256, 1024), c->n_chunks);
+        HIP_TRY(c, hipMemcpyAsync(c->chunk_owner_dev, chunk_to_solver, sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemsetAsync(c->bits_dev, 0, sizeof(unsigned) * (size_t)c->words * (size_t)K, c->stream));
+        hipLaunchKernelGGL(mark_columns, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev, c->words);
+        hipLaunchKernelGGL(prefix_columns, dim3(K), dim3(1024), 0, c->stream, c->bits_dev, c->pref_dev, c->words, c->count_dev);
+        HIP_TRY(c, hipGetLastError());
+        std::vector<int32_t> cnt(K);
+        HIP_TRY(c, hipMemcpyAsync(cnt.data(), c->count_dev, sizeof(int32_t) * (size_t)K, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        std::vector<int64_t> off(K);
+        int64_t used = 0;
+        for (int32_t k = 0; k < K; ++k) { off[k] = used; used += ((int64_t)cnt[k] + 63) / 64 * 64; }
+        if (used > c->u_capacity) return fail(c, CHICLE_ENOMEM, "private vectors need %lld floats, %lld reserved", (long long)used, (long long)c->u_capacity);
+        c->u_used = used;
+        HIP_TRY(c, hipMemcpyAsync(c->u_off_dev, off.data(), sizeof(int64_t) * (size_t)K, hipMemcpyHostToDevice, c->stream));
+        hipLaunchKernelGGL(compact_indices, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev,
+                           c->pref_dev, c->words);
+        HIP_TRY(c, hipGetLastError());
+        HIP_TRY(c, hipStreamSynchronize(c->stream));      // cnt, off and the caller's table go out of scope
         // as many workgroups per solver as the chip has compute units for, each owning a range of columns
         const int k_pad = (K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
         c->cluster = std::max(1, std::min(CLUSTER_MAX, c->cu_count / k_pad));
@@ -1036,8 +1095,13 @@ int chicle_aggregate(chicle_ctx *c)
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "no local epoch pending");
     seg_begin(c, CHICLE_SEG_AGGREGATE);
     const int64_t d4 = c->ld_v / 4;
-    hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w64, c->w,
-                       c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
+    if (c->long_rows)
+        hipLaunchKernelGGL(aggregate_compact, dim3((unsigned)((c->words + AGG_WORDS - 1) / AGG_WORDS)), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
+                           c->u, c->u_off_dev, c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K,
+                           (float)(1.0 / (double)c->K));
+    else
+        hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w64, c->w,
+                           c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
     seg_end(c, CHICLE_SEG_AGGREGATE);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = false;
@@ -1138,8 +1202,12 @@ int chicle_get_delta_w(chicle_ctx *c, int32_t solver, float *dw_out)
     if (!c || !dw_out) return CHICLE_EINVAL;
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "updates exist only between local_epoch and aggregate");
     if (solver < -1 || solver >= c->K) return fail(c, CHICLE_EINVAL, "solver %d, K=%d", solver, c->K);
-    hipLaunchKernelGGL(delta_w_out, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->u, c->ld_v,
-                       (int64_t)c->d, c->K, solver, (float)(1.0 / (double)c->K), c->tmp_a);
+    if (c->long_rows)
+        hipLaunchKernelGGL(delta_w_out_compact, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->u, c->u_off_dev,
+                           c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K, solver, (float)(1.0 / (double)c->K), c->tmp_a);
+    else
+        hipLaunchKernelGGL(delta_w_out, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->u, c->ld_v,
+                           (int64_t)c->d, c->K, solver, (float)(1.0 / (double)c->K), c->tmp_a);
     HIP_TRY(c, hipGetLastError());
     return read_vector(c, c->tmp_a, 1.0f, dw_out);
 }

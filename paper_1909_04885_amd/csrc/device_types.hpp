@@ -26,6 +26,15 @@ struct ChunkDev {
     int64_t nnz;              // stored entries
 };
 
+// Readable entries past the last row of a chunk (kernels read short rows with fixed-width loads), and the
+// length in entries of a chunk's per-entry arrays in the store (a multiple of 64 entries = 256 bytes).
+constexpr int ENTRY_SLACK = 64;
+__host__ __device__ inline int64_t padded_entries(int64_t nnz) { return (nnz + ENTRY_SLACK + 63) / 64 * 64; }
+// Where private vectors are stored compactly (long sparse rows), a chunk's column ids are followed by an
+// array of the same length that holds, for every entry, the index of its column in the compact private
+// vector of the solver that owns the chunk.
+__host__ __device__ inline const int32_t *chunk_compact_ids(const ChunkDev &ch) { return ch.col + padded_entries(ch.nnz); }
+
 // One local solver under the current assignment.
 struct SolverDev {
     int64_t perm_off;         // where this solver's visiting order starts in the concatenated array

@@ -43,6 +43,75 @@ __global__ __launch_bounds__(256) void renumber_rows(const ChunkDev *__restrict_
     }
 }
 
+// ---- compact private vectors (long sparse rows: a solver touches a small part of the columns) ----
+// Per solver a bitmap of the columns its chunks contain and, per 32-column word, the number of set bits
+// before it: column c of solver k lives at index pref[k][c >> 5] + popcount(bits[k][c >> 5] below bit c & 31)
+// of that solver's compact vector.
+
+// bits[owner[chunk]][c >> 5] |= 1 << (c & 31) for every entry.  Grid: (blocks over entries, chunk).
+__global__ __launch_bounds__(256) void mark_columns(const ChunkDev *__restrict__ chunks, const int32_t *__restrict__ owner,
+                                                    unsigned *bits, int64_t words)
+{
+    const ChunkDev &ch = chunks[blockIdx.y];
+    unsigned *mine = bits + (int64_t)owner[blockIdx.y] * words;
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < ch.nnz; p += (int64_t)gridDim.x * 256) {
+        const int c = ch.col[p];
+        atomicOr(mine + (c >> 5), 1u << (c & 31));
+    }
+}
+
+// pref[k][j] = number of set bits in bits[k][0 .. j); count[k] = all of them.  One workgroup of 1024 per solver.
+__global__ __launch_bounds__(1024) void prefix_columns(const unsigned *__restrict__ bits, int32_t *pref, int64_t words,
+                                                       int32_t *count)
+{
+    __shared__ int wave_sum[16];
+    __shared__ int carry;
+    const unsigned *b = bits + (int64_t)blockIdx.x * words;
+    int32_t *p = pref + (int64_t)blockIdx.x * words;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < words; base += 1024) {
+        const int64_t j = base + threadIdx.x;
+        const int v = j < words ? __popc(b[j]) : 0;
+        int incl = v;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o, 64);
+            if ((threadIdx.x & 63) >= o) incl += y;
+        }
+        if ((threadIdx.x & 63) == 63) wave_sum[threadIdx.x >> 6] = incl;
+        __syncthreads();
+        int off = carry;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) off += wave_sum[w];
+        if (j < words) p[j] = off + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = off + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) count[blockIdx.x] = carry;
+}
+
+// The compact index of every entry, written behind the chunk's column ids.  Grid: (blocks over entries, chunk).
+__global__ __launch_bounds__(256) void compact_indices(const ChunkDev *__restrict__ chunks, const int32_t *__restrict__ owner,
+                                                       const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
+                                                       int64_t words)
+{
+    const ChunkDev &ch = chunks[blockIdx.y];
+    const int64_t k = owner[blockIdx.y];
+    const unsigned *b = bits + k * words;
+    const int32_t *pf = pref + k * words;
+    int32_t *out = const_cast<int32_t *>(chunk_compact_ids(ch));
+    const int64_t n = padded_entries(ch.nnz);
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < n; p += (int64_t)gridDim.x * 256) {
+        int idx = 0;                                   // the slack behind the last row points at index 0
+        if (p < ch.nnz) {
+            const int c = ch.col[p];
+            idx = pf[c >> 5] + __popc(b[c >> 5] & ((1u << (c & 31)) - 1u));
+        }
+        out[p] = idx;
+    }
+}
+
 // out[col_of[r]] = in[r] * scale (internal order -> caller's column ids).
 template <typename T>
 __global__ __launch_bounds__(256) void to_caller_order(const T *__restrict__ in,

@@ -160,8 +160,11 @@ template <int LOSS, int BLOCK, int EPT>
 __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
-    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, int max_list, RoundScalars sc, int *err)
+    const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, int max_list, RoundScalars sc, int *err,
+    const int64_t *__restrict__ u_off)
 {
+    // u_off != nullptr: private vectors are stored compactly, solver k's at u_all + u_off[k], and every
+    // entry's index into it is found in the array behind the chunk's column ids
     extern __shared__ __align__(16) unsigned char rw_smem[];
     __shared__ float red[BLOCK / 64];
     __shared__ RowMeta ring[4];
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
     __syncthreads();
-    float *u = u_all + (int64_t)blockIdx.x * ld_v;
+    float *u = u_off ? u_all + u_off[blockIdx.x] : u_all + (int64_t)blockIdx.x * ld_v;
     const int32_t *pk = perm + S.perm_off;
     const int n = S.n_rows;
 
@@ -200,7 +203,8 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
                 const int len = m_rp.y - m_rp.x;
                 if (m_ci >= 0 && m.q != 0.f && len > 0) {
                     const ChunkDev &ch = l_desc[m_ci];
-                    m.col = ch.col + m_rp.x; m.val = ch.val + m_rp.x; m.st = ch.st + m_r; m.len = len;
+                    m.col = (u_off ? chunk_compact_ids(ch) : ch.col) + m_rp.x;
+                    m.val = ch.val + m_rp.x; m.st = ch.st + m_r; m.len = len;
                 }
                 ring[(t + 2) & 3] = m;
             }

@@ -86,8 +86,10 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr_cluster(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
     const int32_t *__restrict__ perm, float *u_all, int64_t ld_v, int max_list, RoundScalars sc, int *err,
-    int k_pad, int G, const int32_t *__restrict__ split, unsigned long long *ring_all)
+    int k_pad, int G, const int32_t *__restrict__ split, unsigned long long *ring_all,
+    const int64_t *__restrict__ u_off)
 {
+    // u_off: as in sdca_rowwise_csr (compact private vectors; the members' runs are still ranges of columns)
     extern __shared__ __align__(16) unsigned char rw_smem[];
     __shared__ float red[BLOCK / 64];
     __shared__ RowMeta ring_rows[4];
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr_cluster(
     }
     if (tid == 0) dead = 0;
     __syncthreads();
-    float *u = u_all + (int64_t)sid * ld_v;
+    float *u = u_off ? u_all + u_off[sid] : u_all + (int64_t)sid * ld_v;
     const int32_t *pk = perm + S.perm_off;
     unsigned long long *ring = ring_all + (int64_t)sid * CLUSTER_WORDS;
     const int n = S.n_rows;
@@ -134,7 +136,8 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr_cluster(
                 if (m_ci >= 0 && m_st.z != 0.f && len > 0) {
                     const ChunkDev &ch = l_desc[m_ci];
                     const int lo = g == 0 ? 0 : m_lo, hi = g == G - 1 ? len : m_hi;
-                    m.col = ch.col + m_rp.x + lo; m.val = ch.val + m_rp.x + lo; m.st = ch.st + m_r;
+                    m.col = (u_off ? chunk_compact_ids(ch) : ch.col) + m_rp.x + lo;
+                    m.val = ch.val + m_rp.x + lo; m.st = ch.st + m_r;
                     m.len = hi - lo;
                     m.q = m_st.z;
                 }
