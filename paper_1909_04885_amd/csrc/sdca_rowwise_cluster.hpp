@@ -162,23 +162,31 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr_cluster(
             // order entry of row t + 4
             p_val = (t + 4 >= 0 && t + 4 < n) ? pk[t + 4] : -1;
         }
-        // this member's entries of row t + 1 (published last step)
+        // The gather of row t is requested first and this member's entries of row t + 1 (published last step)
+        // after it: loads return in the order they were issued, so the step does not wait for the next
+        // row's entries, which come from memory.
+        const RowMeta m = ring_rows[t & 3];                       // (t < 0: an unused slot)
+        const bool step = t >= 0 && m.q != 0.f;                   // the row takes a step (uniform over the cluster)
+        float got[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            got[e] = 0.f;
+            if (step && tid + e * BLOCK < m.len) got[e] = ld_l2(u + c_c[e]);
+        }
         if (t + 1 >= 0 && t + 1 < n) {
-            const RowMeta &m = ring_rows[(t + 1) & 3];
+            const RowMeta &mn = ring_rows[(t + 1) & 3];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 const int p = tid + e * BLOCK;
                 n_c[e] = 0; n_v[e] = 0.f;
-                if (p < m.len) { n_c[e] = gld(m.col + p); n_v[e] = gld(m.val + p); }
+                if (p < mn.len) { n_c[e] = gld(mn.col + p); n_v[e] = gld(mn.val + p); }
             }
         }
-        if (t >= 0) {
-            const RowMeta m = ring_rows[t & 3];
-            if (m.q != 0.f) {                                    // the row takes a step (uniform over the cluster)
+        {
+            if (step) {
                 float part = 0.f;
 #pragma unroll
-                for (int e = 0; e < EPT; ++e)
-                    if (tid + e * BLOCK < m.len) part += c_v[e] * ld_l2(u + c_c[e]);
+                for (int e = 0; e < EPT; ++e) part += c_v[e] * got[e];
                 for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK) part += gld(m.val + p) * ld_l2(u + gld(m.col + p));
                 const float mine = block_sum<BLOCK>(part, red);
                 // exchange the partial sums: slot t % CLUSTER_RING, one word per member
