@@ -76,8 +76,12 @@ enum chicle_solver_kind {
                                      a solver may use all processors of its node) */
     CHICLE_SOLVER_BATCHED = 2,    /* blocks of 64 rows via their Gram matrix, same sequence of steps: sparse rows
                                      of at most 48 entries (dense rows that short are stored that way), or dense
-                                     rows of at most 320 columns; else EINVAL at the pass */
-    CHICLE_SOLVER_ROWWISE_ONE_CU = 3  /* row-wise with every solver on one compute unit */
+                                     rows of at most 320 columns; else EINVAL at the pass.  Where the columns do
+                                     not all fit the part of the private vector a compute unit keeps on chip and
+                                     the chip has compute units to spare, two workgroups share every solver: one
+                                     owns the popular columns and runs the steps, the other owns the rest */
+    CHICLE_SOLVER_ROWWISE_ONE_CU = 3, /* row-wise with every solver on one compute unit */
+    CHICLE_SOLVER_BATCHED_ONE_CU = 4  /* batched with every solver on one compute unit */
 };
 
 /* Timed segments reported by chicle_last_kernel_ms. */

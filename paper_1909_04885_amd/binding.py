@@ -18,7 +18,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, ESTATE, EDEVICE = 0, -1, -2, -3, -4
 LOSS = {"hinge": 0, "squared": 1, "logistic": 2}
-SOLVER = {"auto": 0, "rowwise": 1, "batched": 2, "rowwise_one_cu": 3}
+SOLVER = {"auto": 0, "rowwise": 1, "batched": 2, "rowwise_one_cu": 3, "batched_one_cu": 4}
 SEGMENT = {"local_epoch": 0, "aggregate": 1, "gap": 2, "epoch_gram": 3, "epoch_chain": 4}
 
 EXPORTS = [

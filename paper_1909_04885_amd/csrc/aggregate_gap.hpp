@@ -62,6 +62,9 @@ __global__ __launch_bounds__(256) void delta_w_out(const float *u_all, int64_t l
 // contiguous run of its compact vector, which the workgroup reads (and clears) with coalesced accesses into
 // LDS; each thread then picks the entries of its own word out of the run, in order, by the word's bits.
 // u_off[k]: where solver k's compact vector starts in u.  Reads and clears only what the solvers touched.
+// Where there are few words (few workgroups), the solvers are divided over gridDim.y slices as well; the
+// slices then add their sums into the double-precision vector with atomic adds and the float mirror is
+// refreshed by a pass of its own (mirror_from_double).
 constexpr int AGG_WORDS = 256;                       // words (threads) per workgroup
 __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, float *w32, float *u, const int64_t *__restrict__ u_off,
                                                                const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
@@ -80,12 +83,14 @@ __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, floa
     for (int b = 0; b < 32; ++b) acc[b] = 0.f;
     unsigned any = 0;
     // (the next solver's word and prefix are requested before this solver's run is waited for)
-    unsigned m_next = live && K > 0 ? bits[j] : 0u;
-    int pf_next = live && K > 0 ? pref[j] : 0;
-    for (int k = 0; k < K; ++k) {
+    const int per = (K + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int k0 = (int)blockIdx.y * per, k1 = min(K, k0 + per);
+    unsigned m_next = live && k0 < k1 ? bits[(int64_t)k0 * words + j] : 0u;
+    int pf_next = live && k0 < k1 ? pref[(int64_t)k0 * words + j] : 0;
+    for (int k = k0; k < k1; ++k) {
         const unsigned m = m_next;
         const int pf = pf_next;
-        if (k + 1 < K && live) { m_next = bits[(int64_t)(k + 1) * words + j]; pf_next = pref[(int64_t)(k + 1) * words + j]; }
+        if (k + 1 < k1 && live) { m_next = bits[(int64_t)(k + 1) * words + j]; pf_next = pref[(int64_t)(k + 1) * words + j]; }
         if (tid == 0) run_begin = pf;
         if (tid == last) run_end = pf + __popc(m);
         __syncthreads();
@@ -109,11 +114,22 @@ __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, floa
     for (int i = tid; i < AGG_WORDS * 32; i += AGG_WORDS) {
         const int64_t c = c0 + i;
         if (c < d && (touched[i >> 5] & (1u << (i & 31)))) {
-            const double x = w64[c] + (double)(run[(i >> 5) * 33 + (i & 31)] * inv_sigma);
-            w64[c] = x;
-            w32[c] = (float)x;
+            const double add = (double)(run[(i >> 5) * 33 + (i & 31)] * inv_sigma);
+            if (gridDim.y == 1) {
+                const double x = w64[c] + add;
+                w64[c] = x;
+                w32[c] = (float)x;
+            } else {
+                atomicAdd(&w64[c], add);
+            }
         }
     }
+}
+
+__global__ __launch_bounds__(256) void mirror_from_double(const double *__restrict__ w64, float *w32, int64_t d)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < d; c += stride) w32[c] = (float)w64[c];
 }
 
 // Read-back helper for compact private vectors: out <- Delta w_solver, or sum_k Delta w_k when solver < 0.

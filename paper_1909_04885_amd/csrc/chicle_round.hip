@@ -21,6 +21,7 @@
 #include "policies.hpp"
 #include "sdca_batched.hpp"
 #include "sdca_batched_dense.hpp"
+#include "sdca_batched_split.hpp"
 #include "sdca_rowwise.hpp"
 #include "sdca_rowwise_cluster.hpp"
 
@@ -35,6 +36,9 @@ constexpr int MAX_LIST_LDS = 768;      // chunks one solver may own (their descr
 constexpr int DENSE_V_LDS_MAX_D = 8192;
 constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
+#ifndef SPLIT_TAILS
+#define SPLIT_TAILS 2        // tail workgroups per solver of the split batched solver (1 or 2)
+#endif
 constexpr double LONG_ROW_AVG = 96.0;  // sparse rows longer than this on average: the row-wise solver uses whole workgroups per row
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
@@ -140,6 +144,9 @@ struct chicle_ctx {
     double *gap_host_dev = nullptr;   // ... through this device address
     int *err_dev = nullptr;
     int *progress_dev = nullptr;      // per solver: block its batched pass has reached
+    unsigned long long *split_ring_dev = nullptr;   // per solver: rings between the workgroups that share it
+    bool split_allowed = true;        // the batched solver may spread a solver over several compute units
+    int max_tail_entries = 0;         // most entries a row has outside the columns the batched solver keeps on chip
     // long sparse rows: several workgroups (a cluster) share every solver of the row-wise pass
     bool long_rows = false;           // average row longer than LONG_ROW_AVG
     int32_t *row_split_dev = nullptr; // per row: where the columns of cluster members 1.. begin
@@ -147,7 +154,8 @@ struct chicle_ctx {
     int cluster = 1;                  // members per solver under the current assignment
     int split_built_for = 0;          // cluster size row_split_dev was built for
     bool cluster_allowed = true;
-    // ... and private vectors are stored compactly (a solver touches a small part of the columns)
+    // Sparse chunks: private vectors are stored compactly (a solver touches a small part of the columns)
+    bool compact = false;
     int64_t words = 0;                // 32-column words per bitmap
     unsigned *bits_dev = nullptr;     // max_solvers x words: columns a solver's chunks contain
     int32_t *pref_dev = nullptr;      // max_solvers x words: set bits before each word
@@ -216,7 +224,11 @@ int64_t private_floats(int64_t total_entries, int64_t ld, int32_t max_solvers, b
     return long_rows ? std::min(dense, total_entries + 64 * (int64_t)max_solvers) : dense;
 }
 
-size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows,
+// Columns [0, forced) of a compact vector are always present (the batched solver keeps them on chip and
+// addresses them by column id); at most this many.
+constexpr int64_t COMPACT_FORCED_MAX = LDS_BYTES / sizeof(double);
+
+size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows, bool compact,
                    int64_t n_total_entries_hint)
 {
     const int64_t ld = pad_d(d);
@@ -237,9 +249,12 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(int));
     s += align_up(sizeof(long long) * 2 * (size_t)max_solvers);
     s += align_up(sizeof(int) * (size_t)max_solvers);
+    s += align_up(sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)max_solvers);   // rings of the split batched solver
     if (long_rows) {
         s += align_up(sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         s += align_up(sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+    }
+    if (compact) {
         const size_t words = ((size_t)d + 31) / 32;
         s += 2 * align_up(sizeof(int32_t) * words * (size_t)max_solvers);          // column bitmaps, prefix counts
         s += align_up(sizeof(int32_t) * (size_t)max_solvers) + align_up(sizeof(int64_t) * (size_t)max_solvers);
@@ -248,12 +263,12 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     return s;
 }
 
-size_t chunk_bytes(bool dense, bool long_rows, int64_t n_rows, int64_t entries)
+size_t chunk_bytes(bool dense, bool compact, int64_t n_rows, int64_t entries)
 {
     size_t s = 0;
     if (!dense) {
         s += align_up(sizeof(int32_t) * (size_t)(n_rows + 1));
-        s += align_up(sizeof(int32_t) * (size_t)(entries + ENTRY_SLACK)) * (long_rows ? 2 : 1);   // column ids (+ compact ids)
+        s += align_up(sizeof(int32_t) * (size_t)(entries + ENTRY_SLACK)) * (compact ? 2 : 1);   // column ids (+ compact ids)
     }
     s += align_up(sizeof(float) * (size_t)(entries + ENTRY_SLACK));
     s += align_up(sizeof(RowState) * (size_t)n_rows);
@@ -299,7 +314,7 @@ int grid_for(int64_t items, int per_block, int cap)
 int clear_all_private(chicle_ctx *c)
 {
     if (c->K <= 0) return CHICLE_OK;
-    if (c->long_rows) {
+    if (c->compact) {
         HIP_TRY(c, hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->u_used, c->stream));
         return CHICLE_OK;
     }
@@ -330,6 +345,19 @@ bool dense_as_csr(int32_t d) { return d <= GRAM_MAX_ROW; }
 bool batched_eligible(const chicle_ctx *c)
 {
     return !c->dense && c->max_row_len <= GRAM_MAX_ROW && c->max_list <= BATCHED_MAX_LIST;
+}
+
+// LDS layout of the batched solvers: BatchedShared, the solver's chunk descriptors and row prefixes, then
+// the head of the private vector (the most popular columns, as many as fit), in double.
+struct BatchedLayout { size_t hot_off, bytes; int n_hot; };
+BatchedLayout batched_layout(const chicle_ctx *c)
+{
+    BatchedLayout L;
+    const int ml = std::max(c->max_list, 1);
+    L.hot_off = (sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + 15) & ~(size_t)15;
+    L.n_hot = (int)std::min<int64_t>((int64_t)((LDS_BYTES - L.hot_off) / sizeof(double)) & ~(int64_t)63, c->d);
+    L.bytes = L.hot_off + sizeof(double) * (size_t)L.n_hot;
+    return L;
 }
 
 // Dense rows too wide to be stored with column ids, narrow enough for a block of 64 to sit in LDS.
@@ -384,7 +412,7 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
         } else if (avg <= LONG_ROW_AVG)
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 64, 2>), dim3(c->K), dim3(64), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
-                               perm, c->u, c->ld_v, ml, sc, c->err_dev, (const int64_t *)nullptr);
+                               perm, c->u, c->ld_v, ml, sc, c->err_dev, (const int64_t *)(c->compact ? c->u_off_dev : nullptr));
         else
             hipLaunchKernelGGL((sdca_rowwise_csr<LOSS, 512, 4>), dim3(c->K), dim3(512), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
@@ -435,18 +463,40 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, bool tiles_ready, const i
     c->ahead_tiles = false;
     if (perm_next) HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));   // everything enqueued so far
     const int ml = std::max(c->max_list, 1);
-    const size_t hot_off = (sizeof(BatchedShared) + (sizeof(ChunkDev) + sizeof(int)) * (size_t)ml + 15) & ~(size_t)15;
-    const int n_hot = (int)std::min<int64_t>((int64_t)((LDS_BYTES - hot_off) / sizeof(double)) & ~(int64_t)63, c->d);
-    const size_t sh = hot_off + sizeof(double) * (size_t)n_hot;
-    auto kern = sdca_batched_csr<LOSS>;
-    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
-    const int first_warmer = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
-    HIP_TRY(c, hipMemsetAsync(c->progress_dev, 0, sizeof(int) * (size_t)c->K, c->stream));
-    seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
-    hipLaunchKernelGGL(kern, dim3(first_warmer + c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev,
-                       c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u,
-                       c->ld_v, ml, n_hot, (int)hot_off, sc, c->err_dev, c->progress_dev, first_warmer);
-    seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    const BatchedLayout lay = batched_layout(c);
+    const size_t hot_off = lay.hot_off, sh = lay.bytes;
+    const int n_hot = lay.n_hot;
+    const int64_t *u_off = c->compact ? c->u_off_dev : nullptr;
+    const int k_pad = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
+    // Columns outside the LDS-resident head, and compute units to spare: every solver gets a head workgroup
+    // and SPLIT_TAILS tail workgroups (all of them must be resident together: they wait for each other).
+    const bool split = c->split_allowed && n_hot < c->d && (1 + SPLIT_TAILS) * k_pad <= c->cu_count &&
+                       sizeof(double) * (size_t)n_hot >= 2 * RING * BATCH * sizeof(RowSlot);   // a tail keeps its rows there
+    if (split) {
+        SplitArgs A;
+        A.chunks = c->chunks_dev; A.solvers = c->solvers_dev; A.solver_chunks = c->solver_chunks_dev;
+        A.solver_prefix = c->solver_prefix_dev; A.perm = perm; A.tiles = c->tiles[c->tile_buf]; A.u_all = c->u;
+        A.ld_v = c->ld_v; A.u_off = u_off; A.max_list = ml; A.n_hot = n_hot; A.hot_off = (int)hot_off; A.sc = sc;
+        A.err = c->err_dev; A.n_tails = SPLIT_TAILS; A.xchg_all = c->split_ring_dev;
+        // a tail's helper lanes take the last 24 entries of a row where that covers every row's unpopular columns
+        const bool short_tail = c->compact && c->max_tail_entries <= 3 * LPR;
+        auto kern = short_tail ? sdca_batched_split<LOSS, 3> : sdca_batched_split<LOSS, ENT>;
+        HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+        HIP_TRY(c, hipMemsetAsync(c->split_ring_dev, 0, sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)c->K, c->stream));
+        seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+        hipLaunchKernelGGL(kern, dim3((1 + SPLIT_TAILS) * k_pad), dim3(SPLIT_THREADS), sh, c->stream, A, k_pad);
+        seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    } else {
+        auto kern = sdca_batched_csr<LOSS>;
+        HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+        const int first_warmer = k_pad;
+        HIP_TRY(c, hipMemsetAsync(c->progress_dev, 0, sizeof(int) * (size_t)c->K, c->stream));
+        seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
+        hipLaunchKernelGGL(kern, dim3(first_warmer + c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev,
+                           c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u,
+                           c->ld_v, u_off, ml, n_hot, (int)hot_off, sc, c->err_dev, c->progress_dev, first_warmer);
+        seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
+    }
     HIP_TRY(c, hipGetLastError());
     if (perm_next) {
         // the other tile set was last read by the previous pass's chain kernel, which precedes ev_fork
@@ -611,15 +661,16 @@ size_t chicle_arena_bytes(int64_t n_total, int64_t total_entries, int32_t d, int
 {
     if (n_total <= 0 || total_entries < 0 || d <= 0 || n_chunks <= 0 || max_solvers <= 0) return 0;
     const bool long_rows = !dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
-    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers, long_rows, total_entries);
+    const bool compact = !dense;
+    size_t s = fixed_bytes(n_total, d, n_chunks, max_solvers, long_rows, compact, total_entries);
     // chunk blocks: exact array bytes plus alignment slack per array and chunk
     const size_t per_chunk_slack = 8 * ALIGN + 2 * sizeof(float) * ENTRY_SLACK;
     if (dense && !dense_as_csr(d))
         s += sizeof(float) * (size_t)total_entries + 4 * sizeof(float) * (size_t)n_total;
     else
-        s += (sizeof(int32_t) * (long_rows ? 2 : 1) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
+        s += (sizeof(int32_t) * (compact ? 2 : 1) + sizeof(float)) * ((size_t)total_entries + (size_t)n_chunks) +
              sizeof(int32_t) * ((size_t)n_total + (size_t)n_chunks) + 4 * sizeof(float) * (size_t)n_total;
-    s += (per_chunk_slack + (long_rows ? ALIGN + sizeof(int32_t) * ENTRY_SLACK : 0)) * (size_t)n_chunks;
+    s += (per_chunk_slack + (compact ? ALIGN + sizeof(int32_t) * ENTRY_SLACK : 0)) * (size_t)n_chunks;
     return s + ALIGN;
 }
 
@@ -656,6 +707,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->tmp_a = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
     c->tmp_b = (float *)carve(c, sizeof(float) * (size_t)c->ld_v);
     c->long_rows = !c->api_dense && (double)total_entries > LONG_ROW_AVG * (double)n_total;
+    c->compact = !c->api_dense;
     c->u_capacity = private_floats(total_entries, c->ld_v, max_solvers, c->long_rows);
     c->u = (float *)carve(c, sizeof(float) * (size_t)c->u_capacity);
     c->rank_of = (int32_t *)carve(c, sizeof(int32_t) * (size_t)d);
@@ -677,9 +729,12 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->err_dev = (int *)carve(c, sizeof(int));
     c->ticks_dev = (long long *)carve(c, sizeof(long long) * 2 * (size_t)max_solvers);
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
+    c->split_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)max_solvers);
     if (c->long_rows) {
         c->row_split_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         c->cluster_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
+    }
+    if (c->compact) {
         c->words = ((int64_t)d + 31) / 32;
         c->bits_dev = (unsigned *)carve(c, sizeof(unsigned) * (size_t)c->words * (size_t)max_solvers);
         c->pref_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->words * (size_t)max_solvers);
@@ -687,7 +742,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
         c->u_off_dev = (int64_t *)carve(c, sizeof(int64_t) * (size_t)max_solvers);
         c->chunk_owner_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     }
-    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || (c->long_rows && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || !c->split_ring_dev || (c->long_rows && !c->cluster_ring_dev) || (c->compact && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -726,7 +781,7 @@ static int load_common(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, int64_t 
     if (c->rows_loaded + n_rows > c->n_total) return fail(c, CHICLE_EINVAL, "more rows than n_total");
     if (c->entries_loaded + entries > c->total_entries)
         return fail(c, CHICLE_EINVAL, "more stored entries than total_entries");
-    if (c->used + chunk_bytes(c->dense, c->long_rows, n_rows, entries) > c->arena_bytes)
+    if (c->used + chunk_bytes(c->dense, c->compact, n_rows, entries) > c->arena_bytes)
         return fail(c, CHICLE_ENOMEM, "chunk store full");
     return CHICLE_OK;
 }
@@ -812,7 +867,7 @@ static int load_csr(chicle_ctx *c, int32_t chunk_id, int32_t n_rows, const int32
     int32_t *rp = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(n_rows + 1));
     // a few entries of slack: kernels read short rows with fixed-width vector loads
     int32_t *cd = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
-    if (c->long_rows) {      // compact ids, filled at every assign; must lie where chunk_compact_ids() looks
+    if (c->compact) {      // compact ids, filled at every assign; must lie where chunk_compact_ids() looks
         int32_t *ci = (int32_t *)carve(c, sizeof(int32_t) * (size_t)(nnz + ENTRY_SLACK));
         if (!ci || ci != cd + padded_entries(nnz)) return fail(c, CHICLE_ENOMEM, "chunk store full");
     }
@@ -956,15 +1011,19 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
     c->gap_items = items[c->n_chunks];
     c->state = ST_READY;
     c->cluster = 1;
-    if (c->long_rows) {
+    if (c->compact) {
         // Compact private vectors: which columns each solver's chunks contain, where each of them lives in
-        // the solver's vector, and that index for every stored entry.
+        // the solver's vector, and that index for every stored entry.  The columns the batched solver keeps
+        // on chip are present in every solver's vector, at their own index.
         int64_t max_nnz = 1;
         for (const ChunkDev &ch : c->chunks) max_nnz = std::max(max_nnz, padded_entries(ch.nnz));
         const dim3 egrid(grid_for(max_nnz, 256, 1024), c->n_chunks);
         HIP_TRY(c, hipMemcpyAsync(c->chunk_owner_dev, chunk_to_solver, sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemsetAsync(c->bits_dev, 0, sizeof(unsigned) * (size_t)c->words * (size_t)K, c->stream));
         hipLaunchKernelGGL(mark_columns, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev, c->words);
+        const int forced = batched_eligible(c) ? batched_layout(c).n_hot : 0;
+        if (forced > 0)
+            hipLaunchKernelGGL(force_columns, dim3(K), dim3(256), 0, c->stream, c->bits_dev, c->words, forced);
         hipLaunchKernelGGL(prefix_columns, dim3(K), dim3(1024), 0, c->stream, c->bits_dev, c->pref_dev, c->words, c->count_dev);
         HIP_TRY(c, hipGetLastError());
         std::vector<int32_t> cnt(K);
@@ -979,7 +1038,18 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
         hipLaunchKernelGGL(compact_indices, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev,
                            c->pref_dev, c->words);
         HIP_TRY(c, hipGetLastError());
+        if (forced > 0) {
+            int max_rows = 1;
+            for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
+            HIP_TRY(c, hipMemsetAsync(c->count_dev, 0, sizeof(int32_t), c->stream));
+            hipLaunchKernelGGL(max_entries_beyond, dim3(grid_for(max_rows, 256, 64), c->n_chunks), dim3(256), 0, c->stream,
+                               c->chunks_dev, forced, c->count_dev);
+            HIP_TRY(c, hipGetLastError());
+            HIP_TRY(c, hipMemcpyAsync(&c->max_tail_entries, c->count_dev, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        }
         HIP_TRY(c, hipStreamSynchronize(c->stream));      // cnt, off and the caller's table go out of scope
+    }
+    if (c->long_rows) {
         // as many workgroups per solver as the chip has compute units for, each owning a range of columns
         const int k_pad = (K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
         c->cluster = std::max(1, std::min(CLUSTER_MAX, c->cu_count / k_pad));
@@ -1007,10 +1077,11 @@ int chicle_set_solver(chicle_ctx *c, int32_t kind)
 {
     if (!c) return CHICLE_EINVAL;
     if (kind != CHICLE_SOLVER_AUTO && kind != CHICLE_SOLVER_ROWWISE && kind != CHICLE_SOLVER_BATCHED &&
-        kind != CHICLE_SOLVER_ROWWISE_ONE_CU)
+        kind != CHICLE_SOLVER_ROWWISE_ONE_CU && kind != CHICLE_SOLVER_BATCHED_ONE_CU)
         return fail(c, CHICLE_EINVAL, "unknown solver kind %d", kind);
     c->cluster_allowed = kind != CHICLE_SOLVER_ROWWISE_ONE_CU;
-    c->solver_kind = kind == CHICLE_SOLVER_ROWWISE_ONE_CU ? CHICLE_SOLVER_ROWWISE : kind;
+    c->split_allowed = kind != CHICLE_SOLVER_BATCHED_ONE_CU;
+    c->solver_kind = kind == CHICLE_SOLVER_ROWWISE_ONE_CU ? CHICLE_SOLVER_ROWWISE : kind == CHICLE_SOLVER_BATCHED_ONE_CU ? CHICLE_SOLVER_BATCHED : kind;
     return CHICLE_OK;
 }
 
@@ -1095,11 +1166,16 @@ int chicle_aggregate(chicle_ctx *c)
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "no local epoch pending");
     seg_begin(c, CHICLE_SEG_AGGREGATE);
     const int64_t d4 = c->ld_v / 4;
-    if (c->long_rows)
-        hipLaunchKernelGGL(aggregate_compact, dim3((unsigned)((c->words + AGG_WORDS - 1) / AGG_WORDS)), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
+    if (c->compact) {
+        // few words: the solvers are divided over slices too, so that the chip is filled
+        const unsigned gx = (unsigned)((c->words + AGG_WORDS - 1) / AGG_WORDS);
+        const unsigned gy = (unsigned)std::max(1, std::min(c->K, (int)(1024 / gx)));
+        hipLaunchKernelGGL(aggregate_compact, dim3(gx, gy), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
                            c->u, c->u_off_dev, c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K,
                            (float)(1.0 / (double)c->K));
-    else
+        if (gy > 1)
+            hipLaunchKernelGGL(mirror_from_double, dim3(grid_for(c->d, 256, 2048)), dim3(256), 0, c->stream, c->w64, c->w, (int64_t)c->d);
+    } else
         hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w64, c->w,
                            c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
     seg_end(c, CHICLE_SEG_AGGREGATE);
@@ -1202,7 +1278,7 @@ int chicle_get_delta_w(chicle_ctx *c, int32_t solver, float *dw_out)
     if (!c || !dw_out) return CHICLE_EINVAL;
     if (c->state != ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "updates exist only between local_epoch and aggregate");
     if (solver < -1 || solver >= c->K) return fail(c, CHICLE_EINVAL, "solver %d, K=%d", solver, c->K);
-    if (c->long_rows)
+    if (c->compact)
         hipLaunchKernelGGL(delta_w_out_compact, dim3(grid_for(c->d, 256, 4096)), dim3(256), 0, c->stream, c->u, c->u_off_dev,
                            c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K, solver, (float)(1.0 / (double)c->K), c->tmp_a);
     else

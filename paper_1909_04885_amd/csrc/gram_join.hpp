@@ -4,7 +4,8 @@
 // rows of the same block (jp): T[jp][i] = scale_i s_i s_j (x_i . x_j).  Columns are stored as popularity
 // ranks, so a row's entries split by a range test:
 //   - popular columns (rank < GRAM_DENSE): the window's values go into a small dense matrix in LDS and
-//     their contribution is a register-tiled dense product (most rows have most of these columns);
+//     their contribution is a dense product on the matrix cores, fp32 in and out (the rows share so many
+//     of these columns that the join's lists would be long);
 //   - all other columns: a hash join in LDS.  Entries are inserted into an open-addressing table keyed
 //     by column, counted per slot, laid out as posting lists (row, value) by a scan, and every entry of
 //     a block row walks the short list of its column, adding its products with float atomics in LDS.
@@ -20,7 +21,7 @@
 
 namespace chicle {
 
-constexpr int GRAM_DENSE = 32;                        // columns handled by the dense product
+constexpr int GRAM_DENSE = 64;                        // columns handled by the dense product
 constexpr int GRAM_THREADS = 1024;
 constexpr int GRAM_SLOTS = 8192;                      // hash slots (> window entries, so probing ends)
 constexpr int GRAM_ENTRIES = TILE_W * GRAM_MAX_ROW;   // 6144 entry positions: row slot * 48 + p
@@ -51,7 +52,7 @@ struct GramShared {
     unsigned short start[GRAM_SLOTS];      // entries per slot, then exclusive scan = list begin
     float post_val[GRAM_ENTRIES];          // posting lists grouped by slot: value ...
     unsigned char post_row[GRAM_ENTRIES];  // ... and window row of each member
-    GramRows rows[2];                      // current tile, next tile
+    GramRows rows[3];                      // current tile and the two after it
     int scan[GRAM_THREADS / 64];
 };
 
@@ -137,27 +138,55 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
         if (tid >= BATCH) R.scale[tid - BATCH] = scale;
     };
 
+    // Rows are known two tiles ahead (the lookups of tile + 2 are spread over the phases of the current
+    // tile), entries one tile ahead: a thread holds the same entry positions of the block rows in every
+    // tile, so the 64 rows that are "previous block" in the next tile are already in its registers and only
+    // the next tile's own rows are requested, a whole tile before they are used.
     lookup1(t_begin); lookup2(); lookup3(); lookup4(); publish(sh.rows[0]);
+    lookup1(t_begin + 1); lookup2(); lookup3(); lookup4(); publish(sh.rows[1]);
     __syncthreads();
+    constexpr int HALF = GRAM_EPT / 2;             // entry positions per thread in the previous block's rows
+    int e_col[GRAM_EPT], n_col[HALF];
+    float e_val[GRAM_EPT], n_val[HALF];
+#pragma unroll
+    for (int k = 0; k < GRAM_EPT; ++k) {           // first tile: all 128 rows
+        const int idx = tid + k * GRAM_THREADS;
+        const int s = idx / GRAM_MAX_ROW, p = idx - s * GRAM_MAX_ROW;
+        e_col[k] = gld(sh.rows[0].col[s] + p); e_val[k] = gld(sh.rows[0].val[s] + p);
+    }
 
     for (int tile = t_begin; tile < t_end; ++tile) {
-        GramRows &R = sh.rows[(tile - t_begin) & 1];
-        // ---- issue this thread's entry loads; clear the tables; next tile's lookup, step 1
-        int e_col[GRAM_EPT];
-        float e_val[GRAM_EPT];
+        const int slot = (tile - t_begin) % 3;
+        GramRows &R = sh.rows[slot];
+        // ---- request the next tile's own rows; clear the tables; lookup of tile + 2, step 1
         bool e_live[GRAM_EPT];
 #pragma unroll
         for (int k = 0; k < GRAM_EPT; ++k) {
             const int idx = tid + k * GRAM_THREADS;
             const int s = idx / GRAM_MAX_ROW, p = idx - s * GRAM_MAX_ROW;
-            // unconditional loads (a row without entries points at readable dummy data; the store keeps
-            // slack behind every chunk), masked by e_live afterwards
+            // (loads are unconditional: a row without entries points at readable dummy data and the store
+            // keeps slack behind every chunk; e_live masks them)
             e_live[k] = p < R.len[s];
-            e_col[k] = gld(R.col[s] + p); e_val[k] = gld(R.val[s] + p);
         }
-        lookup1(tile + 1);
-        for (int i = tid; i < GRAM_SLOTS; i += GRAM_THREADS) { sh.keys[i] = EMPTY_KEY; sh.start[i] = 0; }
-        for (int i = tid; i < GRAM_DENSE * TILE_W; i += GRAM_THREADS) (&sh.d.A[0][0])[i] = 0.f;
+        if (tile + 1 < t_end) {
+            const GramRows &N = sh.rows[(slot + 1) % 3];
+#pragma unroll
+            for (int k = 0; k < HALF; ++k) {
+                const int idx = tid + (k + HALF) * GRAM_THREADS;
+                const int s = idx / GRAM_MAX_ROW, p = idx - s * GRAM_MAX_ROW;
+                n_col[k] = gld(N.col[s] + p); n_val[k] = gld(N.val[s] + p);
+            }
+        }
+        lookup1(tile + 2);
+        {
+            // 16-byte stores: keys <- EMPTY_KEY (all ones), start <- 0, A <- 0
+            uint4 *kq = reinterpret_cast<uint4 *>(sh.keys);
+            for (int i = tid; i < GRAM_SLOTS / 4; i += GRAM_THREADS) kq[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
+            uint4 *sq = reinterpret_cast<uint4 *>(sh.start);
+            for (int i = tid; i < GRAM_SLOTS / 8; i += GRAM_THREADS) sq[i] = make_uint4(0u, 0u, 0u, 0u);
+            uint4 *aq = reinterpret_cast<uint4 *>(&sh.d.A[0][0]);
+            for (int i = tid; i < GRAM_DENSE * TILE_W / 4; i += GRAM_THREADS) aq[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
         __syncthreads();
 
         // ---- dense part into A, the rest into the hash table (count per slot)
@@ -193,9 +222,12 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
         // ---- exclusive scan of the slot counts (8 slots per thread), cursors into keys[]
         {
             const int base = tid * (GRAM_SLOTS / GRAM_THREADS);
-            int cnt[GRAM_SLOTS / GRAM_THREADS], sum = 0;
+            static_assert(GRAM_SLOTS / GRAM_THREADS == 8, "a thread's counts are one 16-byte word");
+            const uint4 packed = *reinterpret_cast<const uint4 *>(&sh.start[base]);
+            const unsigned pw[4] = {packed.x, packed.y, packed.z, packed.w};
+            int cnt[8], sum = 0;
 #pragma unroll
-            for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) { cnt[j] = sh.start[base + j]; sum += cnt[j]; }
+            for (int j = 0; j < 8; ++j) { cnt[j] = (pw[j >> 1] >> ((j & 1) * 16)) & 0xffffu; sum += cnt[j]; }
             int incl = sum;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
@@ -206,12 +238,17 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
             __syncthreads();
             int off = incl - sum;
             for (int w = 0; w < (tid >> 6); ++w) off += sh.scan[w];
+            int cur[8];
+            unsigned st[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int j = 0; j < GRAM_SLOTS / GRAM_THREADS; ++j) {
-                sh.start[base + j] = (unsigned short)off;
-                sh.keys[base + j] = off;
+            for (int j = 0; j < 8; ++j) {
+                cur[j] = off;
+                st[j >> 1] |= (unsigned)off << ((j & 1) * 16);
                 off += cnt[j];
             }
+            *reinterpret_cast<uint4 *>(&sh.start[base]) = make_uint4(st[0], st[1], st[2], st[3]);
+            *reinterpret_cast<int4 *>(&sh.keys[base]) = make_int4(cur[0], cur[1], cur[2], cur[3]);
+            *reinterpret_cast<int4 *>(&sh.keys[base + 4]) = make_int4(cur[4], cur[5], cur[6], cur[7]);
         }
         lookup3();
         __syncthreads();
@@ -224,29 +261,39 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
                 sh.post_val[pos] = e_val[k];
                 sh.post_row[pos] = (unsigned char)((tid + k * GRAM_THREADS) / GRAM_MAX_ROW);
             }
-        // ---- dense part: G[jp][i] = sum_h A[h][64 + i] A[h][jp]; thread -> 4 values of i, 2 of jp
+        // ---- dense part: G[jp][i] = sum_h A[h][jp] A[h][64 + i] on the matrix cores (fp32 in and out).  A
+        //      32 x 2 by 2 x 32 product takes A[l % 32][l / 32] and B[l / 32][l % 32] from lane l; wavefront
+        //      w < 8 owns the 32 x 32 block (jp block w / 2, i block w % 2).  The block of own rows 96..127
+        //      against rows 64..95 lies above the diagonal and is not needed.
         {
-            const int i0 = (tid & 15) * 4, j0 = (tid >> 4) * 2;
-            float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            typedef float floatx16 __attribute__((ext_vector_type(16)));
+            const int wv = tid >> 6, lane = tid & 63;
+            const int tj = wv >> 1, ti = wv & 1;
+            const bool mine = wv < 8 && !(tj == 3 && ti == 0);
+            floatx16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            if (mine) {
+                const float *pa = &sh.d.A[lane >> 5][32 * tj + (lane & 31)];
+                const float *pb = &sh.d.A[lane >> 5][BATCH + 32 * ti + (lane & 31)];
 #pragma unroll 8
-            for (int h = 0; h < GRAM_DENSE; ++h) {
-                const float4 ai = *reinterpret_cast<const float4 *>(&sh.d.A[h][BATCH + i0]);
-                const float2 aj = *reinterpret_cast<const float2 *>(&sh.d.A[h][j0]);
-                acc[0][0] += aj.x * ai.x; acc[0][1] += aj.x * ai.y; acc[0][2] += aj.x * ai.z; acc[0][3] += aj.x * ai.w;
-                acc[1][0] += aj.y * ai.x; acc[1][1] += aj.y * ai.y; acc[1][2] += aj.y * ai.z; acc[1][3] += aj.y * ai.w;
+                for (int h = 0; h < GRAM_DENSE; h += 2)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[h * TILE_W], pb[h * TILE_W], acc, 0, 0, 0);
             }
             lookup4();
             __syncthreads();                 // every read of A is done: G may take its place
+            // result layout: register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
+            if (wv < 8) {
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) sh.G[j0 + a][i0 + b] = (double)acc[a][b];
+                for (int r = 0; r < 16; ++r)
+                    sh.G[32 * tj + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)][32 * ti + (lane & 31)] = (double)acc[r];
+            }
         }
         __syncthreads();
 
         // ---- sparse part: every entry of a block row meets the other members of its column's list
 #pragma unroll
-        for (int k = GRAM_EPT / 2; k < GRAM_EPT; ++k) {          // positions of the block rows (64 .. 127)
+        for (int k = HALF; k < GRAM_EPT; ++k) {                  // positions of the block rows (64 .. 127)
             if (e_slot[k] < 0) continue;
             const int i = (tid + k * GRAM_THREADS) / GRAM_MAX_ROW - BATCH;
             const float a = e_val[k];
@@ -264,16 +311,27 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_tiles_join(
                     if (p + j < pe && (sf[j] < BATCH || sf[j] - BATCH < i)) atomicAdd(&sh.G[sf[j]][i], (double)(a * vf[j]));
             }
         }
-        publish(sh.rows[(tile + 1 - t_begin) & 1]);
+        publish(sh.rows[(slot + 2) % 3]);
         __syncthreads();
 
-        // ---- scale and write out, coalesced over i
-        float *out = tiles + (int64_t)tile * TILE_FLOATS;
-        for (int idx = tid; idx < TILE_FLOATS; idx += GRAM_THREADS) {
-            const int jp = idx >> 6, i = idx & 63;
-            float g = 0.f;
-            if (jp < BATCH || jp - BATCH < i) g = (float)sh.G[jp][i] * R.scale[i] * R.sgn[BATCH + i] * R.sgn[jp];
-            out[idx] = g;
+        // ---- scale and write out, coalesced over i (a thread's i is the same for all its values)
+        {
+            float *out = tiles + (int64_t)tile * TILE_FLOATS;
+            const int i = tid & 63;
+            const float si = R.scale[i] * R.sgn[BATCH + i];
+#pragma unroll
+            for (int k = 0; k < TILE_FLOATS / GRAM_THREADS; ++k) {
+                const int jp = (tid >> 6) + k * (GRAM_THREADS / 64);
+                float g = 0.f;
+                if (jp < BATCH || jp - BATCH < i) g = (float)sh.G[jp][i] * si * R.sgn[jp];
+                out[jp * BATCH + i] = g;
+            }
+        }
+        // this tile's own rows are the next tile's previous block; its own rows have arrived by now
+#pragma unroll
+        for (int k = 0; k < HALF; ++k) {
+            e_col[k] = e_col[k + HALF]; e_val[k] = e_val[k + HALF];
+            e_col[k + HALF] = n_col[k]; e_val[k + HALF] = n_val[k];
         }
         __syncthreads();     // G has been read: the next tile may clear A, which lies inside it
     }

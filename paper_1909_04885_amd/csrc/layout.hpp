@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void renumber_rows(const ChunkDev *__restrict_
     }
 }
 
-// ---- compact private vectors (long sparse rows: a solver touches a small part of the columns) ----
+// ---- compact private vectors (sparse rows: a solver touches a small part of the columns) ----
 // Per solver a bitmap of the columns its chunks contain and, per 32-column word, the number of set bits
 // before it: column c of solver k lives at index pref[k][c >> 5] + popcount(bits[k][c >> 5] below bit c & 31)
 // of that solver's compact vector.
@@ -57,6 +57,16 @@ __global__ __launch_bounds__(256) void mark_columns(const ChunkDev *__restrict__
     for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < ch.nnz; p += (int64_t)gridDim.x * 256) {
         const int c = ch.col[p];
         atomicOr(mine + (c >> 5), 1u << (c & 31));
+    }
+}
+
+// Columns [0, n) are present in every solver's vector: sets their bits.  One workgroup per solver.
+__global__ __launch_bounds__(256) void force_columns(unsigned *bits, int64_t words, int n)
+{
+    unsigned *mine = bits + (int64_t)blockIdx.x * words;
+    for (int j = threadIdx.x; j * 32 < n; j += 256) {
+        const int left = n - j * 32;
+        mine[j] |= left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
     }
 }
 
@@ -110,6 +120,21 @@ __global__ __launch_bounds__(256) void compact_indices(const ChunkDev *__restric
         }
         out[p] = idx;
     }
+}
+
+// *out = the largest number of entries any row has at compact indices >= n (the columns the batched solver
+// does not keep on chip).  Grid: (blocks over rows, chunk), one thread per row; *out starts at 0.
+__global__ __launch_bounds__(256) void max_entries_beyond(const ChunkDev *__restrict__ chunks, int n, int *out)
+{
+    const ChunkDev &ch = chunks[blockIdx.y];
+    const int32_t *cid = chunk_compact_ids(ch);
+    int most = 0;
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < ch.n_rows; r += gridDim.x * 256) {
+        int cnt = 0;
+        for (int p = ch.row_ptr[r]; p < ch.row_ptr[r + 1]; ++p) cnt += cid[p] >= n;
+        most = max(most, cnt);
+    }
+    if (most > 0) atomicMax(out, most);
 }
 
 // out[col_of[r]] = in[r] * scale (internal order -> caller's column ids).

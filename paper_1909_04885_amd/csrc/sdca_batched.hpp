@@ -75,6 +75,10 @@ struct BatchedShared {
     float Tw[2][BATCH][BATCH];   // own part of block i's T: [j][lane]
     float Tx[2][BATCH][BATCH];   // cross part of block i+1's T: [j][lane]
     int hb;
+    int dead;                    // split solver: a wait for a partner workgroup has given up
+    int xflag;                   // split solver: iteration whose ring words are in xv
+    int gcount;                  // split solver, tail: helper wavefronts whose gathered values have arrived
+    float xv[BATCH];             // split solver: what the partner sent (steps, or partial dot products)
 };
 
 // The chain: 64 sequential steps of one block.  Lane i owns row i.
@@ -137,7 +141,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     const ChunkDev *__restrict__ chunks, const SolverDev *__restrict__ solvers,
     const int32_t *__restrict__ solver_chunks, const int32_t *__restrict__ solver_prefix,
     const int32_t *__restrict__ perm, const float *__restrict__ tiles, float *u_all, int64_t ld_v,
-    int max_list, int n_hot, int hot_off, RoundScalars sc, int *err, int *progress, int first_warmer)
+    const int64_t *__restrict__ u_off, int max_list, int n_hot, int hot_off, RoundScalars sc, int *err, int *progress, int first_warmer)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     BatchedShared &sh = *reinterpret_cast<BatchedShared *>(smem);
@@ -154,6 +158,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     if (!warmer) stamp_solver(sc, sid, 0);
     for (int i = tid; i < S.n_chunks; i += BATCHED_THREADS) {
         l_desc[i] = chunks[solver_chunks[S.list_begin + i]];
+        if (u_off) l_desc[i].col = chunk_compact_ids(l_desc[i]);     // compact private vector: its indices, not column ids
         l_prefix[i] = solver_prefix[S.list_begin + i];
     }
     if (warmer) {
@@ -163,7 +168,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
         const int wv = tid >> 6, ln = tid & 63;
         if (wv >= WARM_WAVES) return;
         const int n_blocks = (S.n_rows + BATCH - 1) / BATCH;
-        const float *uw = u_all + (int64_t)sid * ld_v;
+        const float *uw = u_off ? u_all + u_off[sid] : u_all + (int64_t)sid * ld_v;
         const int32_t *pkw = perm + S.perm_off;
         for (int b = wv; b < n_blocks; b += WARM_WAVES) {
             // stay within WARM_AHEAD blocks of the solver (its last value ends every wait)
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(BATCHED_THREADS) void sdca_batched_csr(
     for (int i = tid; i < n_hot; i += BATCHED_THREADS) hot[i] = 0.0;
     if (tid == 0) sh.hb = 0;
     __syncthreads();
-    float *u = u_all + (int64_t)sid * ld_v;
+    float *u = u_off ? u_all + u_off[sid] : u_all + (int64_t)sid * ld_v;
     const int32_t *pk = perm + S.perm_off;
     const float *my_tiles = tiles + (int64_t)S.tile_begin * TILE_FLOATS;
     const int nb = (S.n_rows + BATCH - 1) / BATCH;
