@@ -33,7 +33,9 @@ MINI_CASES = [("dense_hinge", "rowwise", False), ("dense_ridge", "rowwise", Fals
               ("elastic", "batched", False), ("sparse_zipf", "batched", True), ("elastic", "batched", True),
               ("dense_ridge", "auto", True), ("dense_hinge", "auto", False), ("dense_hinge", "batched", False),
               # long rows with every solver kept on one compute unit ("rowwise" spreads it over several there)
-              ("sparse_longrow", "rowwise_one_cu", False)]
+              ("sparse_longrow", "rowwise_one_cu", False),
+              # the batched solver with every solver kept on one compute unit
+              ("sparse_zipf", "batched_one_cu", False), ("elastic", "batched_one_cu", True)]
 
 
 @pytest.mark.parametrize("name,solver,ahead", MINI_CASES)
