@@ -34,7 +34,8 @@ constexpr int GAP_PARTS = 8192;        // workgroups (and partial sums) of the g
 constexpr int WSQ_PARTS = 512;
 constexpr int MAX_LIST_LDS = 768;      // chunks one solver may own (their descriptors are staged in LDS)
 constexpr int DENSE_V_LDS_MAX_D = 8192;
-constexpr int BATCHED_MAX_LIST = 128;  // chunk descriptors of one solver the batched solver stages in LDS
+constexpr int BATCHED_MAX_LIST = MAX_LIST_LDS;  // chunk descriptors of one solver the batched solver stages in LDS (they take
+                                               // the place of columns of the private vector's LDS-resident head)
 constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each: short rows only
 #ifndef SPLIT_TAILS
 #define SPLIT_TAILS 2        // tail workgroups per solver of the split batched solver (1 or 2)

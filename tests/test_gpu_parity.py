@@ -98,6 +98,19 @@ def test_full_sparse_longrow(mods):
     run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 17, 63], log=_log)
 
 
+def test_batched_solver_with_long_chunk_lists(mods):
+    """One solver that owns 235 chunks, then three: the batched solver stages a solver's chunk descriptors in
+    LDS, where they take the place of columns of the private vector; no list length sends the pass to the
+    row-wise solver."""
+    oracle_mod, binding = mods
+    cfg = get_config("sparse_zipf", "mini")
+    cfg.update(chunk_rows=128, K=1, schedule=[(0, 1), (2, 3)], rounds=4)
+    p = make_problem(cfg)
+    assert p.n_chunks > 200
+    print("\ncase sparse_zipf mini, %d chunks, K = 1 then 3, batched" % p.n_chunks, flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, solver="batched", check_alpha_every=1, log=_log)
+
+
 def test_gram_tiles_match_their_definition(mods):
     """The batched solver's Gram kernel against x_i . x_j computed with numpy in double."""
     import scipy.sparse as sp
