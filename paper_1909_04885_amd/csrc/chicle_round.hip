@@ -471,21 +471,24 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, bool tiles_ready, const i
     const int k_pad = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
     // Columns outside the LDS-resident head, and compute units to spare: every solver gets a head workgroup
     // and SPLIT_TAILS tail workgroups (all of them must be resident together: they wait for each other).
-    const bool split = c->split_allowed && n_hot < c->d && (1 + SPLIT_TAILS) * k_pad <= c->cu_count &&
-                       sizeof(double) * (size_t)n_hot >= 2 * RING * BATCH * sizeof(RowSlot);   // a tail keeps its rows there
+    // (where every column is in the LDS-resident head there is nothing for tails to do: the head workgroups run
+    // alone, and their gathers and scatters never leave LDS)
+    const int n_tails = n_hot < c->d ? SPLIT_TAILS : 0;
+    const bool split = c->split_allowed && (1 + n_tails) * k_pad <= c->cu_count &&
+                       (n_tails == 0 || sizeof(double) * (size_t)n_hot >= 2 * RING * BATCH * sizeof(RowSlot));   // a tail keeps its rows there
     if (split) {
         SplitArgs A;
         A.chunks = c->chunks_dev; A.solvers = c->solvers_dev; A.solver_chunks = c->solver_chunks_dev;
         A.solver_prefix = c->solver_prefix_dev; A.perm = perm; A.tiles = c->tiles[c->tile_buf]; A.u_all = c->u;
         A.ld_v = c->ld_v; A.u_off = u_off; A.max_list = ml; A.n_hot = n_hot; A.hot_off = (int)hot_off; A.sc = sc;
-        A.err = c->err_dev; A.n_tails = SPLIT_TAILS; A.xchg_all = c->split_ring_dev;
+        A.err = c->err_dev; A.n_tails = n_tails; A.xchg_all = c->split_ring_dev;
         // a tail's helper lanes take the last 24 entries of a row where that covers every row's unpopular columns
         const bool short_tail = c->compact && c->max_tail_entries <= 3 * LPR;
         auto kern = short_tail ? sdca_batched_split<LOSS, 3> : sdca_batched_split<LOSS, ENT>;
         HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
         HIP_TRY(c, hipMemsetAsync(c->split_ring_dev, 0, sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)c->K, c->stream));
         seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
-        hipLaunchKernelGGL(kern, dim3((1 + SPLIT_TAILS) * k_pad), dim3(SPLIT_THREADS), sh, c->stream, A, k_pad);
+        hipLaunchKernelGGL(kern, dim3((1 + n_tails) * k_pad), dim3(SPLIT_THREADS), sh, c->stream, A, k_pad);
         seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
     } else {
         auto kern = sdca_batched_csr<LOSS>;

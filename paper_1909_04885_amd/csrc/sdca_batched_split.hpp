@@ -181,7 +181,7 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
             if (i >= 0 && i < nb) {
                 chain_block<LOSS>(sh, i, lane, x_carry, sc.inv_c);
                 // the tails add these steps into their columns
-                ring_put(x_steps + (i & (SPLIT_RING - 1)) * BATCH + lane, sh.delta[i & 1][lane], i + 1);
+                if (A.n_tails > 0) ring_put(x_steps + (i & (SPLIT_RING - 1)) * BATCH + lane, sh.delta[i & 1][lane], i + 1);
             }
             __syncthreads();
         }
@@ -189,7 +189,7 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
         // What the tail sends for this iteration, fetched by a wavefront that has no other loads in flight
         // (loads return in the order they were issued) and handed on through LDS.
         HEAD_ITERATIONS {
-            if (i + 1 >= 0 && i + 1 < nb) {
+            if (A.n_tails > 0 && i + 1 >= 0 && i + 1 < nb) {
                 const int t = (i + 1) % A.n_tails;                   // the tail that owns block i + 1
                 sh.xv[lane] = ring_get(x_parts + (t * SPLIT_RING + ((i + 1) & (SPLIT_RING - 1))) * BATCH + lane, i + 2,
                                        &sh.dead, A.err);
@@ -279,8 +279,10 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
 #pragma unroll
                 for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o, 64);
                 if (sub == 0) {
-                    wait_flag(&sh.xflag, i + 2);
-                    part += sh.xv[rho];                                   // the tail's share of x_i . u
+                    if (A.n_tails > 0) {
+                        wait_flag(&sh.xflag, i + 2);
+                        part += sh.xv[rho];                               // the tail's share of x_i . u
+                    }
                     const int ring = (i + 1) & (RING - 1);
                     float t0 = 0.f, lo = 0.f, hi = 0.f;
                     if (r.len > 0) {
