@@ -234,39 +234,40 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
         }
         int in_len = 0, hb_target = 0;
         HEAD_ITERATIONS {
+            // 0. what this iteration needs of the rows of blocks i + 2, i - 1 and i + 1 (published at least one
+            //    iteration ago) and the steps of block i - 1, read together: one trip to LDS instead of one per use
+            const bool has_in = i + 2 >= 0 && i + 2 < nb, has_s = i - 1 >= 0 && i - 1 < nb, has_g = i + 1 >= 0 && i + 1 < nb;
+            const RowSlot r_in = sh.rows[(i + 2) & (RING - 1)][rho];
+            const RowSlot r_s = sh.rows[(i - 1) & (RING - 1)][rho];
+            const RowSlot r_g = sh.rows[(i + 1) & (RING - 1)][rho];
+            const float dl = sh.delta[(i - 1) & 1][rho];
             // 1. this lane's segment of the row of block i + 2 (unconditional vector loads)
-            if (i + 2 >= 0 && i + 2 < nb) {
-                const RowSlot &r = sh.rows[(i + 2) & (RING - 1)][rho];
-                const int32_t *cp = r.col + sub;
-                const float *vp = r.val + sub;
-                in_len = r.len;
+            if (has_in) {
+                const int32_t *cp = r_in.col + sub;
+                const float *vp = r_in.val + sub;
+                in_len = r_in.len;
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) { in_c[e] = gld(cp + e * LPR); in_v[e] = gld(vp + e * LPR); }
             } else {
                 in_len = 0;
             }
             // 2. block i - 1 is added to the head of the private vector
-            if (i - 1 >= 0 && i - 1 < nb) {
-                const RowSlot &r = sh.rows[(i - 1) & (RING - 1)][rho];
-                const float dl = sh.delta[(i - 1) & 1][rho];
-                if (r.len > 0 && dl != 0.f) {
-                    const float coef = dl * (LOSS == 1 ? 1.f : r.y) * sc.inv_c;
+            if (has_s && r_s.len > 0 && dl != 0.f) {
+                const float coef = dl * (LOSS == 1 ? 1.f : r_s.y) * sc.inv_c;
 #pragma unroll
-                    for (int e = 0; e < ENT; ++e)
-                        if (s_v[e] != 0.f) atomicAdd(&hot[s_c[e]], (double)(coef * s_v[e]));
-                    if (sub == 0) {
-                        float an = r.alpha + dl;
-                        if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
-                        gst(&r.st->alpha, an);
-                    }
+                for (int e = 0; e < ENT; ++e)
+                    if (s_v[e] != 0.f) atomicAdd(&hot[s_c[e]], (double)(coef * s_v[e]));
+                if (sub == 0) {
+                    float an = r_s.alpha + dl;
+                    if (LOSS != 1) an = fminf(fmaxf(an, 0.f), 1.f);
+                    gst(&r_s.st->alpha, an);
                 }
             }
             // 3. ... completely, before block i + 1 is gathered (LDS traffic only)
             hb_target += HELPER_WAVES;
             helper_barrier_lds(&sh.hb, hb_target);
             // 4. gather block i + 1 (blocks <= i - 1 applied)
-            if (i + 1 >= 0 && i + 1 < nb) {
-                const RowSlot &r = sh.rows[(i + 1) & (RING - 1)][rho];
+            if (has_g) {
                 float got[ENT];
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) {
@@ -285,16 +286,16 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
                     }
                     const int ring = (i + 1) & (RING - 1);
                     float t0 = 0.f, lo = 0.f, hi = 0.f;
-                    if (r.len > 0) {
+                    if (r_g.len > 0) {
                         if (LOSS == 0) {
-                            t0 = (sc.c / r.q) * (r.rw - r.y * part);
-                            lo = -r.alpha; hi = 1.f - r.alpha;
+                            t0 = (sc.c / r_g.q) * (r_g.rw - r_g.y * part);
+                            lo = -r_g.alpha; hi = 1.f - r_g.alpha;
                         } else if (LOSS == 1) {
-                            t0 = (sc.c / (sc.c + r.q)) * (r.rw - r.alpha - part);
+                            t0 = (sc.c / (sc.c + r_g.q)) * (r_g.rw - r_g.alpha - part);
                         } else {
-                            t0 = r.rw - r.y * part;
-                            const float rr = r.q * sc.inv_c;
-                            logistic_step(t0, rr, r.alpha, t0 + rr * (r.alpha - 0.5f), &lo);   // lo: the root for t0
+                            t0 = r_g.rw - r_g.y * part;
+                            const float rr = r_g.q * sc.inv_c;
+                            logistic_step(t0, rr, r_g.alpha, t0 + rr * (r_g.alpha - 0.5f), &lo);   // lo: the root for t0
                         }
                     }
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;
