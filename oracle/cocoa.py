@@ -49,8 +49,10 @@ def _load():
                                                c_vp, c_vp, c_d, c_i64, c_d]
         L.oracle_local_epoch_dense.restype = None
         L.oracle_gap.argtypes = [ctypes.c_int, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
-                                 c_vp, c_d, c_vp]
+                                 c_vp, c_d, c_d, c_vp]
         L.oracle_gap.restype = None
+        L.oracle_soft_threshold.argtypes = [c_i64, c_vp, c_d, c_vp]
+        L.oracle_soft_threshold.restype = None
         L.oracle_assign_greedy.argtypes = [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp]
         L.oracle_assign_greedy.restype = ctypes.c_int
         _lib = L
@@ -115,7 +117,7 @@ class OracleCoCoA:
     """
 
     def __init__(self, loss: str, n: int, d: int, lam: float, y, chunk_bounds,
-                 X=None, row_ptr=None, col=None, val=None):
+                 X=None, row_ptr=None, col=None, val=None, l1: float = 0.0):
         self.L = _load()
         self.loss = _LOSS[loss]
         self.n, self.d, self.lam = int(n), int(d), float(lam)
@@ -127,15 +129,22 @@ class OracleCoCoA:
         self.val = None if val is None else np.ascontiguousarray(val, dtype=np.float32)
         self.alpha = np.zeros(self.n, dtype=np.float64)
         self.w = np.zeros(self.d, dtype=np.float64)
+        # Elastic net (Section 2.2 speaks of generalised linear models in general): regulariser
+        # lambda (|w|^2 / 2 + l1 |w|_1).  The solvers' updates add up in the dual image v; the shared
+        # vector is its soft-thresholded image, w = S_l1(v).  A local pass is unchanged: it starts from
+        # the shared w and its update is linear in the dual steps (the subproblem bounds the conjugate of
+        # the regulariser, which is 1-smooth, by a quadratic around v).  l1 = 0: w = v.
+        self.l1 = float(l1)
+        self.v = np.zeros(self.d, dtype=np.float64)
         self.K = 0
         self.chunk_to_solver = None
         self.rows_of: List[np.ndarray] = []
         self._pending: Optional[np.ndarray] = None   # sum_k Delta w_k awaiting aggregation
 
     @classmethod
-    def from_problem(cls, p):
+    def from_problem(cls, p, l1: float = 0.0):
         return cls(p.loss, p.n, p.d, p.lam, p.y, p.chunk_bounds, X=p.X, row_ptr=p.row_ptr,
-                   col=p.col, val=p.val)
+                   col=p.col, val=p.val, l1=l1)
 
     # ---- scheduler side (between iterations) -------------------------------------------------
     def assign(self, K: int, chunk_to_solver) -> None:
@@ -197,11 +206,17 @@ class OracleCoCoA:
 
     # ---- trainer side ------------------------------------------------------------------------
     def aggregate(self) -> np.ndarray:
-        """w <- w + sum_k Delta w_k (adding, gamma = 1).  Returns the sum that was added."""
+        """v <- v + sum_k Delta w_k (adding, gamma = 1), w <- S_l1(v).  Returns the sum that was added."""
         if self._pending is None:
             raise RuntimeError("nothing to aggregate")
         s = self._pending
-        self.w = self.w + s
+        self.v = self.v + s
+        if self.l1 > 0.0:
+            w = np.empty_like(self.v)
+            self.L.oracle_soft_threshold(self.d, _p(self.v), self.l1, _p(w))
+            self.w = w
+        else:
+            self.w = self.v.copy()
         self._pending = None
         return s
 
@@ -209,5 +224,5 @@ class OracleCoCoA:
         """(P, D, P - D, Fenchel-Young form) at the current (w, alpha)."""
         out = np.zeros(4, dtype=np.float64)
         self.L.oracle_gap(self.loss, self.n, self.d, _p(self.X), _p(self.row_ptr), _p(self.col),
-                          _p(self.val), _p(self.y), _p(self.alpha), _p(self.w), self.lam, _p(out))
+                          _p(self.val), _p(self.y), _p(self.alpha), _p(self.w), self.lam, self.l1, _p(out))
         return tuple(float(x) for x in out)

@@ -123,13 +123,16 @@ void oracle_local_epoch_dense(int loss, int64_t n_local, const int64_t *rows, co
  *   out[0] = P, out[1] = D, out[2] = P - D, out[3] = 1/n sum_i g_i
  * with hinge g_i = max(0, 1 - y_i z_i) - a_i + a_i y_i z_i, squared g_i = (z_i - y_i + a_i)^2 / 2 and
  * logistic g_i = log(1 + exp(-y_i z_i)) + a_i log a_i + (1 - a_i) log(1 - a_i) + a_i y_i z_i.
- * Pass X != NULL for dense rows, else the CSR arrays. */
+ * Pass X != NULL for dense rows, else the CSR arrays.
+ * Elastic-net regulariser lambda (|w|^2 / 2 + l1 |w|_1): w is the soft-thresholded dual image
+ * (see oracle_soft_threshold); the conjugate of the regulariser at the dual image is |w|^2 / 2, so only the
+ * primal value gains a term. */
 void oracle_gap(int loss, int64_t n_total, int64_t d, const float *X, const int64_t *row_ptr,
                 const int32_t *col, const float *val, const float *y, const double *alpha,
-                const double *w, double lambda, double *out)
+                const double *w, double lambda, double l1, double *out)
 {
-    double wsq = 0.0;
-    for (int64_t j = 0; j < d; ++j) wsq += w[j] * w[j];
+    double wsq = 0.0, wabs = 0.0;
+    for (int64_t j = 0; j < d; ++j) { wsq += w[j] * w[j]; wabs += fabs(w[j]); }
     double loss_sum = 0.0, conj_sum = 0.0, fy_sum = 0.0;
     for (int64_t i = 0; i < n_total; ++i) {
         double z = 0.0;
@@ -161,7 +164,7 @@ void oracle_gap(int loss, int64_t n_total, int64_t d, const float *X, const int6
         }
     }
     const double nn = (double)n_total;
-    out[0] = 0.5 * lambda * wsq + loss_sum / nn;
+    out[0] = lambda * (0.5 * wsq + l1 * wabs) + loss_sum / nn;
     out[1] = -0.5 * lambda * wsq - conj_sum / nn;
     out[2] = out[0] - out[1];
     out[3] = fy_sum / nn;
@@ -204,3 +207,14 @@ int oracle_assign_greedy(const int64_t *load, int32_t n_chunks, int32_t K, const
     }
     return 0;
 }
+
+/* Elastic net: the primal vector that belongs to a dual image v under the regulariser
+ * g(w) = |w|^2 / 2 + l1 |w|_1 is the gradient of g's conjugate, w_j = sign(v_j) max(|v_j| - l1, 0). */
+void oracle_soft_threshold(int64_t d, const double *v, double l1, double *w)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        const double a = fabs(v[j]) - l1;
+        w[j] = a > 0.0 ? (v[j] > 0.0 ? a : -a) : 0.0;
+    }
+}
+

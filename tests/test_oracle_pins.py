@@ -493,3 +493,75 @@ def test_zero_chunk_solver_and_bad_tables(oracle_mod):
     o.assign(2, [0, 1, 1])
     with pytest.raises(ValueError):
         o.local_epoch([np.arange(10, dtype=np.int32), np.zeros(20, dtype=np.int32)])
+
+
+# ----------------------------------------------------------------------------- elastic net
+# Regulariser lambda (|w|^2 / 2 + l1 |w|_1) (Section 2.2 speaks of generalised linear models in general).
+# The pins: the lasso-type optimum from scikit-learn's coordinate descent (a different algorithm on the
+# primal), optimality of that point under the oracle's own primal value, weak duality with a gap that
+# closes, the primal vector as the soft-thresholded image of alpha, and l1 = 0 leaving everything as it was.
+def test_elastic_net_squared_loss_matches_coordinate_descent(oracle_mod):
+    from sklearn.linear_model import ElasticNet
+    n, d, lam, l1 = 120, 10, 0.05, 4.0
+    X, y = tiny_dense(n, d, 21, "squared")
+    o = oracle_mod.OracleCoCoA("squared", n, d, lam, y, bounds(n, 16), X=X, l1=l1)
+    hist = run_rounds(o, 3, 3000)
+    # scikit-learn minimises 1/(2n) |y - Xw|^2 + a r |w|_1 + a (1 - r) / 2 |w|^2
+    a, r = lam * (1.0 + l1), l1 / (1.0 + l1)
+    ref = ElasticNet(alpha=a, l1_ratio=r, fit_intercept=False, tol=1e-14, max_iter=1000000)
+    ref.fit(X.astype(np.float64), y.astype(np.float64))
+    assert np.count_nonzero(ref.coef_ == 0.0) >= 1 and np.count_nonzero(ref.coef_) >= 2   # the term bites
+    assert np.linalg.norm(o.w - ref.coef_) < 1e-7 * np.linalg.norm(ref.coef_)
+    assert np.array_equal(o.w == 0.0, ref.coef_ == 0.0)
+    P, D, G, _ = hist[-1]
+    assert -1e-12 <= G < 1e-10
+    # that point is optimal under the oracle's own primal value: no coordinate move of the other solver's
+    # solution lowers it (a wrong weight of the |w|_1 term would move the optimum)
+    o.w = ref.coef_.copy()
+    P0 = o.gap()[0]
+    for j in range(d):
+        for step in (1e-4, -1e-4):
+            o.w = ref.coef_.copy()
+            o.w[j] += step
+            assert o.gap()[0] >= P0 - 1e-13
+
+
+@pytest.mark.parametrize("loss", ["hinge", "logistic"])
+def test_elastic_net_duality(oracle_mod, loss):
+    n, d, lam, l1 = 150, 12, 0.02, 0.8
+    X, y = tiny_dense(n, d, 22, loss)
+    o = oracle_mod.OracleCoCoA(loss, n, d, lam, y, bounds(n, 16), X=X, l1=l1)
+    o.assign(3, np.arange(o.chunk_bounds.size - 1, dtype=np.int32) % 3)
+    Xd, yd = X.astype(np.float64), y.astype(np.float64)
+    prevD, gaps = -np.inf, []
+    for r in range(1500):
+        o.local_epoch(round_permutations(3, r, o.rows_per_solver()), keep_deltas=False)
+        o.aggregate()
+        P, D, G, FY = o.gap()
+        # w is the soft-thresholded image of alpha
+        v = Xd.T @ (o.alpha * yd) / (lam * n)
+        assert np.max(np.abs(o.w - np.sign(v) * np.maximum(np.abs(v) - l1, 0.0))) < 1e-12
+        assert G >= -1e-12 and D >= prevD - 1e-12          # weak duality; adding with sigma = K never lowers D
+        assert abs(G - FY) < 1e-10 * max(1.0, abs(P))      # regulariser and its conjugate meet at w = grad g*(v)
+        prevD = D
+        gaps.append(G)
+    assert gaps[-1] < 1e-4 * gaps[0]                       # ... and the gap closes: P and D bracket the optimum
+    assert np.count_nonzero(o.w == 0.0) >= 1
+    # the primal value at that w is minimal against a derivative-free search from it (non-smooth objective)
+    def Pw(w):
+        z = Xd @ w
+        l = np.maximum(0.0, 1.0 - yd * z) if loss == "hinge" else np.logaddexp(0.0, -yd * z)
+        return l.mean() + lam * (0.5 * w @ w + l1 * np.abs(w).sum())
+    res = scipy.optimize.minimize(Pw, o.w, method="Powell", options={"xtol": 1e-10, "ftol": 1e-14, "maxiter": 20000})
+    assert res.fun >= o.gap()[1] - 1e-9                    # nothing found below the dual value
+    assert res.fun >= Pw(o.w) - 2.0 * gaps[-1]             # ... nor more than the remaining gap below the oracle's point
+    assert abs(Pw(o.w) - o.gap()[0]) < 1e-12
+
+
+def test_elastic_net_with_zero_l1_is_the_plain_round(oracle_mod):
+    n, d, lam = 90, 7, 0.03
+    X, y = tiny_dense(n, d, 23, "hinge")
+    a = oracle_mod.OracleCoCoA("hinge", n, d, lam, y, bounds(n, 16), X=X)
+    b = oracle_mod.OracleCoCoA("hinge", n, d, lam, y, bounds(n, 16), X=X, l1=0.0)
+    ha, hb = run_rounds(a, 2, 20), run_rounds(b, 2, 20)
+    assert ha == hb and np.array_equal(a.w, b.w) and np.array_equal(a.alpha, b.alpha)
