@@ -209,6 +209,16 @@ int chicle_solver_rows(chicle_ctx *ctx, int64_t *rows_out);
 /* Select the local-solver kernel (chicle_solver_kind); default AUTO. */
 int chicle_set_solver(chicle_ctx *ctx, int32_t kind);
 
+/* Elastic net (Section 2.2: the method covers generalised linear models with a strongly convex
+ * regulariser): the objective becomes (1/n) sum_i loss_i(x_i . w) + lambda (|w|^2 / 2 + l1 |w|_1).  The
+ * solvers' updates then add up in the dual image v (kept in double), the shared vector every solver
+ * starts from is w_j = sign(v_j) max(|v_j| - l1, 0), the local pass is unchanged, the primal value gains
+ * lambda l1 |w|_1 and the dual value uses |w|^2 / 2 as the regulariser's conjugate at v.  l1 = 0 (the
+ * default) is the plain L2 round.  Legal in LOADING and READY; in READY the shared vector is recomputed
+ * from v with the new threshold.  Afterwards chicle_set_w is refused while l1 > 0 (w does not determine
+ * v).  Errors: EINVAL (negative or not finite), ESTATE (between local_epoch and aggregate). */
+int chicle_set_l1(chicle_ctx *ctx, double l1);
+
 /* One local pass of all K solvers, concurrently, each from the current w (Section 2.2; Section 4.2).
  * perm_device: device array of n_total int32: solver 0's visiting order (a permutation of
  * [0, rows_0)), then solver 1's, and so on.  Commits alpha in the chunks and leaves the solver's update

@@ -29,7 +29,7 @@ EXPORTS = [
     "chicle_get_assignment", "chicle_debug_gram", "chicle_sync", "chicle_set_profiling",
     "chicle_last_kernel_ms", "chicle_last_error", "chicle_destroy",
     "chicle_solver_ms", "chicle_projected_iteration_time", "chicle_scale_out", "chicle_scale_in",
-    "chicle_rebalance", "chicle_next_solver_count", "chicle_gap_noalloc",
+    "chicle_rebalance", "chicle_next_solver_count", "chicle_gap_noalloc", "chicle_set_l1",
 ]
 
 
@@ -67,6 +67,7 @@ def load_library():
         "chicle_assign": (ctypes.c_int, [vp, i32, vp]),
         "chicle_solver_rows": (ctypes.c_int, [vp, vp]),
         "chicle_set_solver": (ctypes.c_int, [vp, i32]),
+        "chicle_set_l1": (ctypes.c_int, [vp, dbl]),
         "chicle_local_epoch": (ctypes.c_int, [vp, vp]),
         "chicle_local_epoch_ahead": (ctypes.c_int, [vp, vp, vp]),
         "chicle_local_epoch_host_perm": (ctypes.c_int, [vp, vp]),
@@ -276,6 +277,10 @@ class ChicleRound:
 
     def set_solver(self, kind: str):
         self._check(self._L.chicle_set_solver(self._h, SOLVER[kind]))
+
+    def set_l1(self, l1: float):
+        """Elastic net: regulariser lambda (|w|^2 / 2 + l1 |w|_1); 0 is the plain L2 round."""
+        self._check(self._L.chicle_set_l1(self._h, float(l1)))
 
     # -- the round
     def upload_perm(self, perms):

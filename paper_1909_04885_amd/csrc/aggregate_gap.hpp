@@ -8,6 +8,18 @@
 
 namespace chicle {
 
+// Elastic net (paper Section 2.2: generalised linear models): with the regulariser lambda (|w|^2 / 2 +
+// l1 |w|_1) the solvers' updates add up in the dual image v, which is what the double-precision vector
+// holds, and the shared vector is w_j = sign(v_j) max(|v_j| - l1, 0).  l1 = 0: w = v.
+__device__ __forceinline__ double soft_threshold(double v, double l1)
+{
+    const double a = fabs(v) - l1;
+    return a > 0.0 ? copysign(a, v) : 0.0;
+}
+// The shared vector as the gap kernels read it: the float mirror holds w itself, the double vector holds v.
+__device__ __forceinline__ float shared_at(const float *w, int64_t c, double) { return w[c]; }
+__device__ __forceinline__ double shared_at(const double *v, int64_t c, double l1) { return soft_threshold(v[c], l1); }
+
 // u_k <- 0 for k < K (a solver fetching the model starts with no update of its own).
 __global__ __launch_bounds__(256) void clear_private(float *u_all, int64_t ld_v, int64_t d4, int K)
 {
@@ -22,7 +34,7 @@ __global__ __launch_bounds__(256) void clear_private(float *u_all, int64_t ld_v,
 // One pass: reads K + 1 vectors, writes K + 2 vectors, four columns per thread (ld_v and the
 // buffers are 16-byte aligned; d is handled up to its padded length, the padding holds zeros).
 __global__ __launch_bounds__(256) void aggregate_broadcast(double *w64, float *w32, float *u_all,
-                                                           int64_t ld_v, int64_t d4, int K, float inv_sigma)
+                                                           int64_t ld_v, int64_t d4, int K, float inv_sigma, double l1)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     double2 *wd = reinterpret_cast<double2 *>(w64);
@@ -40,7 +52,8 @@ __global__ __launch_bounds__(256) void aggregate_broadcast(double *w64, float *w
         lo.x += (double)(acc.x * inv_sigma); lo.y += (double)(acc.y * inv_sigma);
         hi.x += (double)(acc.z * inv_sigma); hi.y += (double)(acc.w * inv_sigma);
         wd[2 * j] = lo; wd[2 * j + 1] = hi;
-        wf[j] = make_float4((float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y);
+        wf[j] = make_float4((float)soft_threshold(lo.x, l1), (float)soft_threshold(lo.y, l1),
+                            (float)soft_threshold(hi.x, l1), (float)soft_threshold(hi.y, l1));
     }
 }
 
@@ -68,7 +81,7 @@ __global__ __launch_bounds__(256) void delta_w_out(const float *u_all, int64_t l
 constexpr int AGG_WORDS = 256;                       // words (threads) per workgroup
 __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, float *w32, float *u, const int64_t *__restrict__ u_off,
                                                                const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
-                                                               int64_t words, int64_t d, int K, float inv_sigma)
+                                                               int64_t words, int64_t d, int K, float inv_sigma, double l1)
 {
     __shared__ float run[AGG_WORDS * 33];            // a run is at most all columns of the workgroup (32 per word;
                                                      // 33: the sums are laid out one word per padded row at the end)
@@ -118,7 +131,7 @@ __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, floa
             if (gridDim.y == 1) {
                 const double x = w64[c] + add;
                 w64[c] = x;
-                w32[c] = (float)x;
+                w32[c] = (float)soft_threshold(x, l1);
             } else {
                 atomicAdd(&w64[c], add);
             }
@@ -126,10 +139,10 @@ __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, floa
     }
 }
 
-__global__ __launch_bounds__(256) void mirror_from_double(const double *__restrict__ w64, float *w32, int64_t d)
+__global__ __launch_bounds__(256) void mirror_from_double(const double *__restrict__ w64, float *w32, int64_t d, double l1)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < d; c += stride) w32[c] = (float)w64[c];
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < d; c += stride) w32[c] = (float)soft_threshold(w64[c], l1);
 }
 
 // Read-back helper for compact private vectors: out <- Delta w_solver, or sum_k Delta w_k when solver < 0.
@@ -209,7 +222,7 @@ __device__ __forceinline__ void gap_row_terms(RowState *st, WT z, double &s_loss
 // stride and keeps two rows in flight.  Partial sums are indexed by the linear workgroup id.
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__ chunks,
-                                                    const WT *__restrict__ w,
+                                                    const WT *__restrict__ w, double l1,
                                                     double *part_loss, double *part_conj)
 {
     constexpr int GROUPS = 256 / LPR;
@@ -234,8 +247,8 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
             float v0 = 0.f, v1 = 0.f;
             if (p0 < e0) { c0 = col[p0]; v0 = val[p0]; }
             if (p1 < e1) { c1 = col[p1]; v1 = val[p1]; }
-            z0 += (WT)v0 * w[c0];
-            z1 += (WT)v1 * w[c1];
+            z0 += (WT)v0 * shared_at(w, c0, l1);
+            z1 += (WT)v1 * shared_at(w, c1, l1);
             p0 += LPR; p1 += LPR;
         }
 #pragma unroll
@@ -258,7 +271,7 @@ constexpr int GAP_HOT_MAX_LPR = 16;         // lanes per row at most; a lane tak
 
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkDev *__restrict__ chunks,
-                                                                    const WT *__restrict__ w, int n_hot,
+                                                                    const WT *__restrict__ w, double l1, int n_hot,
                                                                     double *part_loss, double *part_conj)
 {
     extern __shared__ __align__(16) unsigned char gap_hot_raw[];
@@ -278,7 +291,7 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
     const int32_t *__restrict__ col = ch.col;
     const float *__restrict__ val = ch.val;
     const int stride = gridDim.x * GROUPS;
-    for (int i = threadIdx.x; i < n_hot; i += GAP_HOT_THREADS) hot[i] = w[i];
+    for (int i = threadIdx.x; i < n_hot; i += GAP_HOT_THREADS) hot[i] = shared_at(w, i, l1);
     __syncthreads();
     double s_loss = 0.0, s_conj = 0.0;
     // (the trip count is the same for all lanes of a wavefront: the shuffles below need every lane)
@@ -304,8 +317,8 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
             for (int k = 0; k < 4; ++k) {
                 const bool in0 = p0 + k < e0, in1 = p1 + k < e1;
                 const int a0 = in0 ? c0[k] : 0, a1 = in1 ? c1[k] : 0;
-                w0[k] = a0 < n_hot ? hot[a0] : w[a0];
-                w1[k] = a1 < n_hot ? hot[a1] : w[a1];
+                w0[k] = a0 < n_hot ? hot[a0] : shared_at(w, a0, l1);
+                w1[k] = a1 < n_hot ? hot[a1] : shared_at(w, a1, l1);
                 if (!in0) v0[k] = 0.f;
                 if (!in1) v1[k] = 0.f;
             }
@@ -343,7 +356,7 @@ __global__ __launch_bounds__(GAP_HOT_THREADS) void gap_rows_csr_hot(const ChunkD
 // Dense rows: LPR lanes per row, strided over the d columns.  Same grid as the sparse kernel.
 template <int LOSS, int LPR, typename WT>
 __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict__ chunks, int d,
-                                                      const WT *__restrict__ w,
+                                                      const WT *__restrict__ w, double l1,
                                                       double *part_loss, double *part_conj)
 {
     constexpr int GROUPS = 256 / LPR;
@@ -354,7 +367,7 @@ __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict
     for (int r = blockIdx.x * GROUPS + grp; r < ch.n_rows; r += gridDim.x * GROUPS) {
         const float *x = ch.val + (int64_t)r * d;
         WT z = 0;
-        for (int p = sub; p < d; p += LPR) z += (WT)x[p] * w[p];
+        for (int p = sub; p < d; p += LPR) z += (WT)x[p] * shared_at(w, p, l1);
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, 64);
         if (sub == 0) gap_row_terms<LOSS, WT>(ch.st + r, z, s_loss, s_conj);
@@ -363,38 +376,40 @@ __global__ __launch_bounds__(256) void gap_rows_dense(const ChunkDev *__restrict
     block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);
 }
 
-// |w|^2 partials in double.
-__global__ __launch_bounds__(256) void wsq_partial(const double *__restrict__ w, int64_t d,
-                                                   double *part_wsq, double *part_unused)
+// |w|^2 and |w|_1 partials in double (w = the soft-thresholded image of the double vector).
+__global__ __launch_bounds__(256) void wsq_partial(const double *__restrict__ v, int64_t d, double l1,
+                                                   double *part_wsq, double *part_wabs)
 {
-    double s = 0.0;
+    double s = 0.0, t = 0.0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
-        const double x = w[j];
+        const double x = soft_threshold(v[j], l1);
         s += x * x;
+        t += fabs(x);
     }
-    block_sum2_store(s, 0.0, &part_wsq[blockIdx.x], &part_unused[blockIdx.x]);
+    block_sum2_store(s, t, &part_wsq[blockIdx.x], &part_wabs[blockIdx.x]);
 }
 
-// out[0] = sum loss, out[1] = sum conj, out[2] = |w|^2, out[3] = the kernels' error flag; one workgroup,
+// out[0] = sum loss, out[1] = sum conj, out[2] = |w|^2, out[3] = the kernels' error flag, out[4] = |w|_1; one workgroup,
 // fixed summation order.  out may be host memory mapped into the device's address space.
 __global__ __launch_bounds__(256) void gap_finish(const double *part_loss, const double *part_conj,
-                                                  int n_row_parts, const double *part_wsq,
+                                                  int n_row_parts, const double *part_wsq, const double *part_wabs,
                                                   int n_w_parts, const int *err, double *out)
 {
-    double a = 0.0, b = 0.0, c = 0.0;
+    double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
     for (int i = threadIdx.x; i < n_row_parts; i += 256) { a += part_loss[i]; b += part_conj[i]; }
-    for (int i = threadIdx.x; i < n_w_parts; i += 256) c += part_wsq[i];
-    __shared__ double ra[4], rb[4], rc[4];
-    a = wave_sum_d(a); b = wave_sum_d(b); c = wave_sum_d(c);
+    for (int i = threadIdx.x; i < n_w_parts; i += 256) { c += part_wsq[i]; e += part_wabs[i]; }
+    __shared__ double ra[4], rb[4], rc[4], re[4];
+    a = wave_sum_d(a); b = wave_sum_d(b); c = wave_sum_d(c); e = wave_sum_d(e);
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { ra[wave] = a; rb[wave] = b; rc[wave] = c; }
+    if ((threadIdx.x & 63) == 0) { ra[wave] = a; rb[wave] = b; rc[wave] = c; re[wave] = e; }
     __syncthreads();
     if (threadIdx.x == 0) {
         out[0] = ra[0] + ra[1] + ra[2] + ra[3];
         out[1] = rb[0] + rb[1] + rb[2] + rb[3];
         out[2] = rc[0] + rc[1] + rc[2] + rc[3];
         out[3] = (double)*err;
+        out[4] = re[0] + re[1] + re[2] + re[3];
     }
 }
 

@@ -102,6 +102,7 @@ struct chicle_ctx {
     int32_t d = 0;
     int64_t ld_v = 0;
     double lambda = 0;
+    double l1 = 0;             // elastic net: regulariser lambda (|w|^2 / 2 + l1 |w|_1); w64 then holds the dual image
     int32_t n_chunks = 0, max_solvers = 0;
     bool dense = false;        // chunks stored as dense row-major matrices
     bool api_dense = false;    // chunks arrive through chicle_load_chunk_dense
@@ -227,7 +228,6 @@ int64_t private_floats(int64_t total_entries, int64_t ld, int32_t max_solvers, b
 
 // Columns [0, forced) of a compact vector are always present (the batched solver keeps them on chip and
 // addresses them by column id); at most this many.
-constexpr int64_t COMPACT_FORCED_MAX = LDS_BYTES / sizeof(double);
 
 size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows, bool compact,
                    int64_t n_total_entries_hint)
@@ -539,7 +539,7 @@ void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w, const GapScratch 
         const int need = (c->max_row_len + 3) / 4;
 #define CHICLE_GAP_HOT(L)                                                                                   \
         hipLaunchKernelGGL((gap_rows_csr_hot<LOSS, L, WT>), hg, dim3(GAP_HOT_THREADS), sh, c->stream,      \
-                           c->chunks_dev, w, n_hot, gs.loss, gs.conj)
+                           c->chunks_dev, w, c->l1, n_hot, gs.loss, gs.conj)
         if (need <= 4) CHICLE_GAP_HOT(4);
         else if (need <= 8) CHICLE_GAP_HOT(8);
         else if (need <= 10) CHICLE_GAP_HOT(10);
@@ -548,9 +548,9 @@ void launch_gap_rows_t(chicle_ctx *c, int grid_x, const WT *w, const GapScratch 
 #undef CHICLE_GAP_HOT
     } else if (c->dense)
         hipLaunchKernelGGL((gap_rows_dense<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev,
-                           (int)c->d, w, gs.loss, gs.conj);
+                           (int)c->d, w, c->l1, gs.loss, gs.conj);
     else
-        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev, w,
+        hipLaunchKernelGGL((gap_rows_csr<LOSS, LPRG, WT>), grid, dim3(256), 0, c->stream, c->chunks_dev, w, c->l1,
                            gs.loss, gs.conj);
 }
 
@@ -765,7 +765,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     }
     for (int s = 0; ok && s < CHICLE_SEG_COUNT; ++s)
         ok = hipEventCreate(&c->seg[s].start) == hipSuccess && hipEventCreate(&c->seg[s].stop) == hipSuccess;
-    ok = ok && hipHostMalloc((void **)&c->gap_host, sizeof(double) * 4, hipHostMallocMapped) == hipSuccess &&
+    ok = ok && hipHostMalloc((void **)&c->gap_host, sizeof(double) * 8, hipHostMallocMapped) == hipSuccess &&
          hipHostGetDevicePointer((void **)&c->gap_host_dev, c->gap_host, 0) == hipSuccess;
     ok = ok && static_scratch_of_current_device(&c->static_scratch) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
@@ -1089,6 +1089,21 @@ int chicle_set_solver(chicle_ctx *c, int32_t kind)
     return CHICLE_OK;
 }
 
+int chicle_set_l1(chicle_ctx *c, double l1)
+{
+    if (!c) return CHICLE_EINVAL;
+    if (!(l1 >= 0.0) || !std::isfinite(l1)) return fail(c, CHICLE_EINVAL, "l1 must be finite and >= 0");
+    if (c->state == ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "aggregate first");
+    c->l1 = l1;
+    if (c->state != ST_LOADING) {      // the shared vector is the threshold's image of what the solvers have summed so far
+        hipLaunchKernelGGL(mirror_from_double, dim3(grid_for(c->d, 256, 2048)), dim3(256), 0, c->stream, c->w64, c->w,
+                           (int64_t)c->d, c->l1);
+        HIP_TRY(c, hipGetLastError());
+        c->zw_valid = false;
+    }
+    return CHICLE_OK;
+}
+
 int chicle_local_epoch(chicle_ctx *c, const int32_t *perm_device)
 {
     if (!c) return CHICLE_EINVAL;
@@ -1176,12 +1191,12 @@ int chicle_aggregate(chicle_ctx *c)
         const unsigned gy = (unsigned)std::max(1, std::min(c->K, (int)(1024 / gx)));
         hipLaunchKernelGGL(aggregate_compact, dim3(gx, gy), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
                            c->u, c->u_off_dev, c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K,
-                           (float)(1.0 / (double)c->K));
+                           (float)(1.0 / (double)c->K), c->l1);
         if (gy > 1)
-            hipLaunchKernelGGL(mirror_from_double, dim3(grid_for(c->d, 256, 2048)), dim3(256), 0, c->stream, c->w64, c->w, (int64_t)c->d);
+            hipLaunchKernelGGL(mirror_from_double, dim3(grid_for(c->d, 256, 2048)), dim3(256), 0, c->stream, c->w64, c->w, (int64_t)c->d, c->l1);
     } else
         hipLaunchKernelGGL(aggregate_broadcast, dim3(grid_for(d4, 256, 4096)), dim3(256), 0, c->stream, c->w64, c->w,
-                           c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K));
+                           c->u, c->ld_v, d4, c->K, (float)(1.0 / (double)c->K), c->l1);
     seg_end(c, CHICLE_SEG_AGGREGATE);
     HIP_TRY(c, hipGetLastError());
     c->zw_valid = false;
@@ -1197,9 +1212,9 @@ static int gap_with(chicle_ctx *c, const GapScratch &gs, double *primal, double 
     int rc = run_row_pass(c, &grid, gs);
     if (rc) { seg_end(c, CHICLE_SEG_GAP); return rc; }
     const int gw = grid_for(c->d, 256 * 8, WSQ_PARTS);
-    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, gs.wsq, gs.unused);
+    hipLaunchKernelGGL(wsq_partial, dim3(gw), dim3(256), 0, c->stream, c->w64, (int64_t)c->d, c->l1, gs.wsq, gs.unused);
     hipLaunchKernelGGL(gap_finish, dim3(1), dim3(256), 0, c->stream, gs.loss, gs.conj, grid,
-                       gs.wsq, gw, c->err_dev, c->gap_host_dev);
+                       gs.wsq, gs.unused, gw, c->err_dev, c->gap_host_dev);
     seg_end(c, CHICLE_SEG_GAP);
     HIP_TRY(c, hipGetLastError());
     // the sums and the error flag arrive in pinned host memory with the end of the kernel: no copy to wait for
@@ -1215,7 +1230,7 @@ static int gap_with(chicle_ctx *c, const GapScratch &gs, double *primal, double 
         return fail(c, CHICLE_EDEVICE, "kernel error flag %d", flag);
     }
     const double n = (double)c->n_total;
-    const double P = 0.5 * c->lambda * h[2] + h[0] / n;
+    const double P = c->lambda * (0.5 * h[2] + c->l1 * h[4]) + h[0] / n;     // (the regulariser's conjugate at the dual image is |w|^2 / 2)
     const double D = -0.5 * c->lambda * h[2] - h[1] / n;
     if (primal) *primal = P;
     if (dual) *dual = D;
@@ -1266,6 +1281,7 @@ int chicle_set_w(chicle_ctx *c, const float *w_in)
     if (!c || !w_in) return CHICLE_EINVAL;
     if (c->state == ST_EPOCH_DONE) return fail(c, CHICLE_ESTATE, "aggregate first");
     if (c->state == ST_LOADING) return fail(c, CHICLE_ESTATE, "assign first (the column order is fixed at the first assign)");
+    if (c->l1 > 0.0) return fail(c, CHICLE_ESTATE, "with l1 > 0 the state is the dual image, which w does not determine");
     for (int32_t j = 0; j < c->d; ++j)
         if (!std::isfinite(w_in[j])) return fail(c, CHICLE_EINVAL, "w not finite at %d", j);
     HIP_TRY(c, hipMemcpyAsync(c->tmp_b, w_in, sizeof(float) * (size_t)c->d, hipMemcpyHostToDevice, c->stream));

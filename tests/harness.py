@@ -59,20 +59,23 @@ def greedy_tables(cfg, p, oracle_mod, binding_mod):
 
 
 def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sample_solvers=None,
-                 check_alpha_every=0, log=None, ahead=False, tables=None, max_solvers=None):
+                 check_alpha_every=0, log=None, ahead=False, tables=None, max_solvers=None, l1=0.0):
     """`sample_solvers`: None compares every solver's Delta w in every round; a list compares every solver
     in the first, the middle and the last round and those of the list in the others (the summed update is
     compared in every round either way).  Returns a list of per-round records; raises AssertionError on the
     first violation.
 
     `tables(r, K_prev, table_prev)` returns None (no change before round r) or (K, table from the
-    oracle side, table from the library side); default: the configured greedy schedule."""
-    o = oracle_mod.OracleCoCoA.from_problem(p)
+    oracle side, table from the library side); default: the configured greedy schedule.
+    `l1` > 0: the elastic-net regulariser lambda (|w|^2 / 2 + l1 |w|_1) on both sides."""
+    o = oracle_mod.OracleCoCoA.from_problem(p, l1=l1)
     maxK = max_solvers or max(k for _, k in cfg["schedule"])
     tables = tables or greedy_tables(cfg, p, oracle_mod, binding_mod)
     table = None
     g = binding_mod.ChicleRound.from_problem(p, max_solvers=maxK)
     g.set_solver(solver)
+    if l1:
+        g.set_l1(l1)
     rounds = cfg["rounds"] if rounds is None else rounds
     K = None
     rec = []
@@ -128,7 +131,7 @@ def run_lockstep(cfg, p, oracle_mod, binding_mod, rounds=None, solver="auto", sa
         Pg, Dg, Gg = g.gap()
         Po, Do, Go, _ = o.gap()
         e_w = rel_l2(g.get_w(), o.w, 1e-30)
-        rec.append(dict(round=r, K=K, dw_err=worst[0], dw_sum_err=e_sum, w_err=e_w,
+        rec.append(dict(round=r, K=K, dw_err=worst[0], dw_sum_err=e_sum, w_err=e_w, w_zero=float(np.mean(o.w == 0.0)),
                         gap_gpu=Gg, gap_ref=Go, P_gpu=Pg, P_ref=Po, D_gpu=Dg, D_ref=Do))
         if log:
             log("r=%d K=%d dw_err=%.2e sum_err=%.2e w_err=%.2e gap gpu=%.6e ref=%.6e" %

@@ -98,6 +98,55 @@ def test_full_sparse_longrow(mods):
     run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 17, 63], log=_log)
 
 
+@pytest.mark.parametrize("name,loss,solver,ahead,l1", [
+    ("dense_hinge", "hinge", "auto", False, 0.5), ("dense_ridge", "squared", "auto", True, 1.5),
+    ("dense_hinge", "logistic", "auto", False, 0.5),
+    ("sparse_zipf", "hinge", "rowwise", False, 0.1), ("sparse_zipf", "hinge", "batched", True, 0.1),
+    ("sparse_zipf", "squared", "batched", False, 0.1), ("sparse_zipf", "logistic", "batched", True, 0.15),
+    ("sparse_zipf", "squared", "batched_one_cu", False, 0.1),
+    ("sparse_longrow", "hinge", "rowwise", False, 0.02), ("sparse_longrow", "logistic", "rowwise_one_cu", False, 0.02),
+    ("elastic", "hinge", "batched", True, 0.1)])
+def test_elastic_net_every_round(mods, name, loss, solver, ahead, l1):
+    """Regulariser lambda (|w|^2 / 2 + l1 |w|_1): the merged updates live in the dual image, every solver starts
+    from its soft-thresholded image, and primal and dual value carry the L1 term and the conjugate; every
+    kernel family that reads or writes the shared vector, each loss, with l1 chosen so that a good part of
+    the coordinates (and not all) sit at exactly zero."""
+    import dataclasses
+    oracle_mod, binding = mods
+    cfg, p = cached_problem(name, "mini")
+    p = dataclasses.replace(p, loss=loss)
+    print("\ncase", name, "mini", loss, solver, "l1=%g n=%d d=%d" % (l1, p.n, p.d), flush=True)
+    rec = run_lockstep(cfg, p, oracle_mod, binding, solver=solver, check_alpha_every=1, log=_log, ahead=ahead, l1=l1)
+    assert 0.1 < rec[-1]["w_zero"] < 0.9
+    for r in rec:
+        assert abs(r["P_gpu"] - r["P_ref"]) <= 1e-5 * abs(r["P_ref"]) + 1e-7
+        assert abs(r["D_gpu"] - r["D_ref"]) <= 1e-5 * abs(r["D_ref"]) + 1e-6
+
+
+def test_elastic_net_setter_contract(mods):
+    """l1 is refused when negative and between a local pass and its merge; with l1 > 0 the shared vector cannot
+    be set from outside; changing l1 in READY re-thresholds the shared vector."""
+    oracle_mod, binding = mods
+    p = _tiny(binding, loss="squared")
+    g = binding.ChicleRound.from_problem(p, max_solvers=3)
+    with pytest.raises(binding.ChicleError):
+        g.set_l1(-1.0)
+    g.set_l1(0.05)                                              # legal before the first assignment too
+    g.assign(3, np.array([0, 1, 2, 0, 1], dtype=np.int32))
+    perms = round_permutations(3, 0, [int(x) for x in g.solver_rows()])
+    g.local_epoch_host_perm(np.concatenate(perms))
+    with pytest.raises(binding.ChicleError):
+        g.set_l1(0.1)
+    g.aggregate()
+    w_a = g.get_w()
+    with pytest.raises(binding.ChicleError):
+        g.set_w(np.zeros(p.d, dtype=np.float32))
+    g.set_l1(0.0)
+    v = g.get_w().astype(np.float64)
+    assert np.allclose(w_a, np.sign(v) * np.maximum(np.abs(v) - 0.05, 0.0), atol=1e-6)
+    g.close()
+
+
 def test_batched_solver_with_long_chunk_lists(mods):
     """One solver that owns 235 chunks, then three: the batched solver stages a solver's chunk descriptors in
     LDS, where they take the place of columns of the private vector; no list length sends the pass to the
