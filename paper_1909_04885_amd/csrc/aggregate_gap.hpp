@@ -139,6 +139,69 @@ __global__ __launch_bounds__(AGG_WORDS) void aggregate_compact(double *w64, floa
     }
 }
 
+// The same merge for thinly occupied vectors (long rows over many columns: a solver holds a few of every
+// hundred columns).  A solver's run for a workgroup's 8192 columns is then a few hundred floats, and staging
+// it through LDS costs three workgroup barriers and a dependent trip to memory per solver.  Here every thread
+// picks the entries of its own word straight from memory - neighbouring threads read neighbouring short
+// pieces of the run, so the lines are shared inside the wavefront - and keeps its 32 sums in LDS (row tid of
+// a padded array, touched by that thread alone until the end), with no barrier inside the walk over the
+// solvers; the next solver's word and prefix are requested before this solver's entries are waited for.
+__global__ __launch_bounds__(AGG_WORDS) void aggregate_compact_thin(double *w64, float *w32, float *u, const int64_t *__restrict__ u_off,
+                                                                    const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
+                                                                    int64_t words, int64_t d, int K, float inv_sigma, double l1)
+{
+    __shared__ float sums[AGG_WORDS * 33];
+    __shared__ unsigned touched[AGG_WORDS];
+    const int tid = threadIdx.x;
+    const int64_t j = (int64_t)blockIdx.x * AGG_WORDS + tid;
+    const bool live = j < words;
+    float *mine = sums + tid * 33;
+#pragma unroll
+    for (int b = 0; b < 32; ++b) mine[b] = 0.f;
+    unsigned any = 0;
+    const int per = (K + (int)gridDim.y - 1) / (int)gridDim.y;              // slices of solvers, as above
+    const int k0 = (int)blockIdx.y * per, k1 = min(K, k0 + per);
+    unsigned m_next = live && k0 < k1 ? bits[(int64_t)k0 * words + j] : 0u;
+    int pf_next = live && k0 < k1 ? pref[(int64_t)k0 * words + j] : 0;
+    for (int k = k0; k < k1; ++k) {
+        unsigned m = m_next;
+        const int pf = pf_next;
+        if (k + 1 < k1 && live) { m_next = bits[(int64_t)(k + 1) * words + j]; pf_next = pref[(int64_t)(k + 1) * words + j]; }
+        any |= m;
+        float *uk = u + u_off[k] + pf;
+        while (m) {                                  // four entries per trip
+            float v[4];
+            int b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                b[q] = m ? __ffs(m) - 1 : -1;
+                m &= m - 1;
+                v[q] = b[q] >= 0 ? uk[q] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (b[q] >= 0) { uk[q] = 0.f; mine[b[q]] += v[q]; }
+            uk += 4;
+        }
+    }
+    touched[tid] = any;
+    __syncthreads();
+    const int64_t c0 = (int64_t)blockIdx.x * AGG_WORDS * 32;
+    for (int i = tid; i < AGG_WORDS * 32; i += AGG_WORDS) {
+        const int64_t c = c0 + i;
+        if (c < d && (touched[i >> 5] & (1u << (i & 31)))) {
+            const double add = (double)(sums[(i >> 5) * 33 + (i & 31)] * inv_sigma);
+            if (gridDim.y == 1) {
+                const double x = w64[c] + add;
+                w64[c] = x;
+                w32[c] = (float)soft_threshold(x, l1);
+            } else {
+                atomicAdd(&w64[c], add);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void mirror_from_double(const double *__restrict__ w64, float *w32, int64_t d, double l1)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -257,6 +320,108 @@ __global__ __launch_bounds__(256) void gap_rows_csr(const ChunkDev *__restrict__
             gap_row_terms<LOSS, WT>(ch.st + r0, z0, s_loss, s_conj);
             if (two) gap_row_terms<LOSS, WT>(ch.st + r1, z1, s_loss, s_conj);
         }
+    }
+    const int part = blockIdx.y * gridDim.x + blockIdx.x;
+    block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);
+}
+
+// ---- the row pass for long rows over a shared vector far larger than a cache ------------------------------
+// A row of a thousand entries spread over twenty million columns makes a thousand lonely 4-byte reads of the
+// shared vector, every one of which misses the L2 cache of its compute-unit group and moves a whole line
+// over the fabric.  Here the columns are cut into slices of 2 MB of the shared vector.  Rows are sorted by
+// column, so a row's entries inside a slice are one contiguous run; off[s * n_total + row] = first entry of the
+// row (relative to its start) with column >= s << shift, for s = 0 .. S, is built once per data set.
+// Workgroup 8 i + x takes slice 8 (i / n_items) + x: the eight cache partitions (workgroups are dealt round
+// robin over them) work on eight neighbouring slices of the same rows at the same time, each partition
+// keeps its own slice of the shared vector in its L2, and the lines of entries that two neighbouring slices
+// share are fetched from memory once.  Partial dot products are added into z[row] with atomic adds; a second
+// kernel turns z into the rows' residuals and the loss and conjugate sums, and clears z for the next pass.
+constexpr int SLICE_BYTES_LOG2 = 21;
+constexpr int SLICE_SEG = 256;                      // rows per workgroup
+constexpr int SLICE_LANES = 16;                     // lanes per row
+constexpr int SLICE_ROWS_IN_FLIGHT = 8;             // rows a lane group works on at the same time
+
+// Grid: (workgroups over rows, chunks); one wavefront per row.
+__global__ __launch_bounds__(256) void slice_offsets(const ChunkDev *__restrict__ chunks, int shift, int S,
+                                                     int64_t n_total, int32_t *off)
+{
+    const ChunkDev &ch = chunks[blockIdx.y];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = blockIdx.x * 4 + wave; r < ch.n_rows; r += gridDim.x * 4) {
+        const int b = ch.row_ptr[r], e = ch.row_ptr[r + 1];
+        int32_t *o = off + ch.row_base + r;
+        // entry p opens every slice after its predecessor's up to its own; the row's end opens all that remain
+        for (int p = b + lane; p <= e; p += 64) {
+            const int sp = p < e ? ch.col[p] >> shift : S;
+            const int sq = p > b ? ch.col[p - 1] >> shift : -1;
+            for (int t = sq + 1; t <= sp; ++t) o[(int64_t)t * n_total] = p - b;
+        }
+    }
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void gap_rows_sliced(const ChunkDev *__restrict__ chunks, const WT *__restrict__ w,
+                                                       double l1, const int32_t *__restrict__ off, int64_t n_total,
+                                                       int S, int segs_per_chunk, int n_items, WT *z)
+{
+    __shared__ int s_b[SLICE_SEG], s_e[SLICE_SEG];
+    const int x = (int)blockIdx.x % L2_PARTITIONS, i = (int)blockIdx.x / L2_PARTITIONS;
+    const int slice = L2_PARTITIONS * (i / n_items) + x, item = i % n_items;
+    if (slice >= S) return;
+    const ChunkDev &ch = chunks[item / segs_per_chunk];
+    const int r0 = (item % segs_per_chunk) * SLICE_SEG;
+    if (r0 >= ch.n_rows) return;
+    const int nr = min(SLICE_SEG, ch.n_rows - r0);
+    const int t = threadIdx.x;
+    if (t < nr) {
+        const int start = ch.row_ptr[r0 + t];
+        const int64_t row = (int64_t)ch.row_base + r0 + t;
+        s_b[t] = start + off[(int64_t)slice * n_total + row];
+        s_e[t] = start + off[(int64_t)(slice + 1) * n_total + row];
+    }
+    __syncthreads();
+    const int32_t *__restrict__ col = ch.col;
+    const float *__restrict__ val = ch.val;
+    const int sub = t % SLICE_LANES, grp = t / SLICE_LANES;
+    constexpr int GROUPS = 256 / SLICE_LANES, RF = SLICE_ROWS_IN_FLIGHT;
+    for (int rb = grp; rb < nr; rb += GROUPS * RF) {
+        int b[RF], e[RF], c[RF];
+        float v[RF];
+        WT acc[RF];
+#pragma unroll
+        for (int k = 0; k < RF; ++k) {
+            const int r = rb + k * GROUPS;
+            b[k] = r < nr ? s_b[r] : 0;
+            e[k] = r < nr ? s_e[r] : 0;
+            const bool has = b[k] + sub < e[k];
+            c[k] = has ? col[b[k] + sub] : 0;
+            v[k] = has ? val[b[k] + sub] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < RF; ++k) acc[k] = (WT)v[k] * shared_at(w, c[k], l1);
+#pragma unroll
+        for (int k = 0; k < RF; ++k)                 // runs longer than the lane group
+            for (int p = b[k] + SLICE_LANES + sub; p < e[k]; p += SLICE_LANES) acc[k] += (WT)val[p] * shared_at(w, col[p], l1);
+#pragma unroll
+        for (int k = 0; k < RF; ++k) {
+#pragma unroll
+            for (int o = SLICE_LANES / 2; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+            if (sub == 0 && e[k] > b[k]) atomicAdd(&z[(int64_t)ch.row_base + r0 + rb + k * GROUPS], acc[k]);
+        }
+    }
+}
+
+// Grid: (workgroups per chunk, chunks); a thread per row.  Partial sums by linear workgroup id, as above.
+template <int LOSS, typename WT>
+__global__ __launch_bounds__(256) void gap_rows_from_z(const ChunkDev *__restrict__ chunks, WT *z,
+                                                       double *part_loss, double *part_conj)
+{
+    const ChunkDev &ch = chunks[blockIdx.y];
+    double s_loss = 0.0, s_conj = 0.0;
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < ch.n_rows; r += gridDim.x * 256) {
+        const WT zi = z[(int64_t)ch.row_base + r];
+        z[(int64_t)ch.row_base + r] = (WT)0;
+        gap_row_terms<LOSS, WT>(ch.st + r, zi, s_loss, s_conj);
     }
     const int part = blockIdx.y * gridDim.x + blockIdx.x;
     block_sum2_store(s_loss, s_conj, &part_loss[part], &part_conj[part]);

@@ -40,6 +40,7 @@ constexpr int RENUMBER_MAX_ROW = 64;   // rows are re-sorted by one thread each:
 #ifndef SPLIT_TAILS
 #define SPLIT_TAILS 2        // tail workgroups per solver of the split batched solver (1 or 2)
 #endif
+constexpr int SLICES_MIN = 4;         // fewer slices of the shared vector than this: the plain gap row pass
 constexpr double LONG_ROW_AVG = 96.0;  // sparse rows longer than this on average: the row-wise solver uses whole workgroups per row
 
 enum State { ST_LOADING = 0, ST_READY = 1, ST_EPOCH_DONE = 2 };
@@ -155,6 +156,9 @@ struct chicle_ctx {
     unsigned long long *cluster_ring_dev = nullptr;
     int cluster = 1;                  // members per solver under the current assignment
     int split_built_for = 0;          // cluster size row_split_dev was built for
+    int32_t *slice_off_dev = nullptr; // long rows: (slices + 1) x n_total run boundaries of the sliced gap row pass
+    double *slice_z_dev = nullptr;    // n_total partial dot products (float or double), zero between passes
+    int gap_slices = 0, gap_slice_shift = 0;   // 0: the sliced row pass is not in use
     bool cluster_allowed = true;
     // Sparse chunks: private vectors are stored compactly (a solver touches a small part of the columns)
     bool compact = false;
@@ -229,6 +233,13 @@ int64_t private_floats(int64_t total_entries, int64_t ld, int32_t max_solvers, b
 // Columns [0, forced) of a compact vector are always present (the batched solver keeps them on chip and
 // addresses them by column id); at most this many.
 
+// Slices of the sliced gap row pass at most (the shared vector in double).
+int max_slices(int32_t d)
+{
+    const int shift = SLICE_BYTES_LOG2 - 3;
+    return (int)(((int64_t)d + (1 << shift) - 1) >> shift);
+}
+
 size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_solvers, bool long_rows, bool compact,
                    int64_t n_total_entries_hint)
 {
@@ -252,6 +263,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     s += align_up(sizeof(int) * (size_t)max_solvers);
     s += align_up(sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)max_solvers);   // rings of the split batched solver
     if (long_rows) {
+        s += align_up(sizeof(int32_t) * ((size_t)max_slices(d) + 1) * (size_t)n_total) + align_up(sizeof(double) * (size_t)n_total);
         s += align_up(sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         s += align_up(sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
     }
@@ -594,7 +606,25 @@ int run_row_pass(chicle_ctx *c, int *grid_out, const GapScratch &gs)
                                   gs.parts / c->n_chunks));
         c->gap_hot_grid = gx;
     }
-    if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx, gs);
+    if (c->gap_slices > 0) {
+        const int segs = (max_rows + SLICE_SEG - 1) / SLICE_SEG, n_items = segs * c->n_chunks;
+        const unsigned blocks = (unsigned)((c->gap_slices + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS) * (unsigned)n_items;
+        gx = std::max(1, std::min((max_rows + 255) / 256, gs.parts / c->n_chunks));
+        const dim3 fg(gx, c->n_chunks);
+        if (c->loss == CHICLE_LOSS_HINGE) {
+            float *z = (float *)c->slice_z_dev;
+            hipLaunchKernelGGL(gap_rows_sliced<float>, dim3(blocks), dim3(256), 0, c->stream, c->chunks_dev, (const float *)c->w, c->l1,
+                               c->slice_off_dev, c->n_total, c->gap_slices, segs, n_items, z);
+            hipLaunchKernelGGL((gap_rows_from_z<0, float>), fg, dim3(256), 0, c->stream, c->chunks_dev, z, gs.loss, gs.conj);
+        } else {
+            hipLaunchKernelGGL(gap_rows_sliced<double>, dim3(blocks), dim3(256), 0, c->stream, c->chunks_dev, (const double *)c->w64, c->l1,
+                               c->slice_off_dev, c->n_total, c->gap_slices, segs, n_items, c->slice_z_dev);
+            if (c->loss == CHICLE_LOSS_SQUARED)
+                hipLaunchKernelGGL((gap_rows_from_z<1, double>), fg, dim3(256), 0, c->stream, c->chunks_dev, c->slice_z_dev, gs.loss, gs.conj);
+            else
+                hipLaunchKernelGGL((gap_rows_from_z<2, double>), fg, dim3(256), 0, c->stream, c->chunks_dev, c->slice_z_dev, gs.loss, gs.conj);
+        }
+    } else if (c->loss == CHICLE_LOSS_HINGE) launch_gap_lpr<0>(c, gx, gs);
     else if (c->loss == CHICLE_LOSS_SQUARED) launch_gap_lpr<1>(c, gx, gs);
     else launch_gap_lpr<2>(c, gx, gs);
     HIP_TRY(c, hipGetLastError());
@@ -735,6 +765,8 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
     c->progress_dev = (int *)carve(c, sizeof(int) * (size_t)max_solvers);
     c->split_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)max_solvers);
     if (c->long_rows) {
+        c->slice_off_dev = (int32_t *)carve(c, sizeof(int32_t) * ((size_t)max_slices(d) + 1) * (size_t)n_total);
+        c->slice_z_dev = (double *)carve(c, sizeof(double) * (size_t)n_total);
         c->row_split_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)SPLITS_PER_ROW * (size_t)n_total);
         c->cluster_ring_dev = (unsigned long long *)carve(c, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)max_solvers);
     }
@@ -746,7 +778,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
         c->u_off_dev = (int64_t *)carve(c, sizeof(int64_t) * (size_t)max_solvers);
         c->chunk_owner_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     }
-    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || !c->split_ring_dev || (c->long_rows && !c->cluster_ring_dev) || (c->compact && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || !c->split_ring_dev || (c->long_rows && (!c->cluster_ring_dev || !c->slice_z_dev)) || (c->compact && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -756,6 +788,7 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
               hipMemsetAsync(c->tmp_b, 0, sizeof(float) * (size_t)c->ld_v, c->stream) == hipSuccess &&
               hipMemsetAsync(c->u, 0, sizeof(float) * (size_t)c->u_capacity, c->stream) == hipSuccess &&
               hipMemsetAsync(c->err_dev, 0, sizeof(int), c->stream) == hipSuccess &&
+              (!c->long_rows || hipMemsetAsync(c->slice_z_dev, 0, sizeof(double) * (size_t)n_total, c->stream) == hipSuccess) &&
               hipMemsetAsync(c->ticks_dev, 0, sizeof(long long) * 2 * (size_t)max_solvers, c->stream) == hipSuccess;
     {
         int dev = 0;
@@ -1065,6 +1098,19 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
             HIP_TRY(c, hipGetLastError());
             c->split_built_for = c->cluster;
         }
+        // the sliced gap row pass, where the shared vector is several slices long (built once: data only)
+        if (c->gap_slices == 0) {
+            const int shift = SLICE_BYTES_LOG2 - (c->loss == CHICLE_LOSS_HINGE ? 2 : 3);
+            const int S = (int)(((int64_t)c->d + (1 << shift) - 1) >> shift);
+            if (S >= SLICES_MIN) {
+                int max_rows = 1;
+                for (const ChunkDev &ch : c->chunks) max_rows = std::max(max_rows, ch.n_rows);
+                hipLaunchKernelGGL(slice_offsets, dim3(grid_for(max_rows, 4, 256), c->n_chunks), dim3(256), 0, c->stream,
+                                   c->chunks_dev, shift, S, c->n_total, c->slice_off_dev);
+                HIP_TRY(c, hipGetLastError());
+                c->gap_slices = S; c->gap_slice_shift = shift;
+            }
+        }
     }
     return clear_all_private(c);
 }
@@ -1189,6 +1235,13 @@ int chicle_aggregate(chicle_ctx *c)
         // few words: the solvers are divided over slices too, so that the chip is filled
         const unsigned gx = (unsigned)((c->words + AGG_WORDS - 1) / AGG_WORDS);
         const unsigned gy = (unsigned)std::max(1, std::min(c->K, (int)(1024 / gx)));
+        // thinly occupied vectors (under an eighth of the columns per solver on average): entries are picked
+        // straight from memory
+        if (c->u_used * 8 < (int64_t)c->K * (int64_t)c->d)
+            hipLaunchKernelGGL(aggregate_compact_thin, dim3(gx, gy), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
+                               c->u, c->u_off_dev, c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K,
+                               (float)(1.0 / (double)c->K), c->l1);
+        else
         hipLaunchKernelGGL(aggregate_compact, dim3(gx, gy), dim3(AGG_WORDS), 0, c->stream, c->w64, c->w,
                            c->u, c->u_off_dev, c->bits_dev, c->pref_dev, c->words, (int64_t)c->d, c->K,
                            (float)(1.0 / (double)c->K), c->l1);

@@ -61,6 +61,8 @@ __device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int solver,
 }
 __device__ __forceinline__ void stamp_solver(const RoundScalars &sc, int which) { stamp_solver(sc, blockIdx.x, which); }
 
+constexpr int L2_PARTITIONS = 8;         // workgroup i is dispatched to L2 partition (compute-unit group) i mod 8
+
 constexpr int ERR_PERM_RANGE = 1;
 constexpr int ERR_PARTNER_TIMEOUT = 2;   // the workgroups that share a solver lost each other
 

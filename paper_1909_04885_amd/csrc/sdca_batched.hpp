@@ -40,7 +40,6 @@ constexpr int RING = 8;
 constexpr int LDS_BYTES = 160 * 1024;
 constexpr int WARM_AHEAD = 6;                 // blocks a warming workgroup may run ahead of its solver
 constexpr int WARM_WAVES = 4;                 // its wavefronts at work
-constexpr int L2_PARTITIONS = 8;              // workgroup i is dispatched to partition i mod 8
 
 // What the helpers know about one row of a block.
 struct RowSlot {

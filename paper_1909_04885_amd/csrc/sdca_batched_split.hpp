@@ -66,6 +66,18 @@ __device__ __forceinline__ void helper_barrier_lds(int *cnt, int target)
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
+// Sum over the LPR = 8 lanes that share a row, in every one of them, by data-parallel-primitive moves (the
+// neighbour inside pairs, the other pair of the quad, then the mirrored half of the eight): register to
+// register, where a shuffle goes through the LDS crossbar and costs a trip's latency each time.
+__device__ __forceinline__ float sum_over_row_lanes(float v)
+{
+    static_assert(LPR == 8, "the moves below cover groups of eight lanes");
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false));   // row_half_mirror
+    return v;
+}
+
 // Wait until an LDS word that only grows has reached `target`.
 __device__ __forceinline__ void wait_flag(const int *flag, int target)
 {
@@ -174,7 +186,7 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
         stamp_solver(sc, sid, 1);
         return;
     }
-#define HEAD_ITERATIONS for (int i = -5; i <= nb; ++i)
+#define HEAD_ITERATIONS for (int i = -6; i <= nb; ++i)
     if (wave == 0) {
         float x_carry = 0.f;
         HEAD_ITERATIONS {
@@ -210,7 +222,9 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
             float4 *dst = reinterpret_cast<float4 *>(sw == 0 ? &sh.Tw[buf][0][0] : &sh.Tx[buf][0][0]);
 #pragma unroll
             for (int j = 0; j < 16; ++j) dst[lane + 64 * j] = staged ? stage[j] : make_float4(0.f, 0.f, 0.f, 0.f);
-            if (sw == 0) resolver.step(sh.rows, RING - 1, l_desc, l_prefix, S, pk, i, 0, 1, nb, lane, A.err, true);
+            // (one block further ahead than the tails' resolvers: the helpers ask for a block's entries three
+            // iterations before they gather it)
+            if (sw == 0) resolver.step(sh.rows, RING - 1, l_desc, l_prefix, S, pk, i + 1, 0, 1, nb, lane, A.err, true);
             const int tb = sw == 0 ? i + 2 : i + 3;
             staged = tb >= 0 && tb < nb;
             if (staged) {
@@ -222,34 +236,38 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
             __syncthreads();
         }
     } else {
-        // Entries of a row segment (ENT entries per helper lane) travel through four stages:
-        // in (loads in flight) -> g (gathered this iteration) -> c (its block is in the chain) -> s (scattered).
-        // Only entries in the head's columns are kept; the others are masked when the set comes in.
-        int in_c[ENT], g_c[ENT], c_c[ENT], s_c[ENT];
-        float in_v[ENT], g_v[ENT], c_v[ENT], s_v[ENT];
+        // Entries of a row segment (ENT entries per helper lane) travel through five stages:
+        // ld (loads in flight) -> ar (arrived: asked for one iteration ago) -> g (gathered this iteration) ->
+        // c (its block is in the chain) -> s (scattered).  Loads get a whole iteration before anything looks at
+        // them; ld and ar swap register sets from one iteration to the next (nothing moves a register that a
+        // load is still due to write).  Only entries in the head's columns are kept; the others are masked when
+        // the set leaves ar.
+        int a_c[ENT], b_c[ENT], g_c[ENT], c_c[ENT], s_c[ENT];
+        float a_v[ENT], b_v[ENT], g_v[ENT], c_v[ENT], s_v[ENT];
 #pragma unroll
         for (int e = 0; e < ENT; ++e) {
-            in_c[e] = g_c[e] = c_c[e] = s_c[e] = 0;
-            in_v[e] = g_v[e] = c_v[e] = s_v[e] = 0.f;
+            a_c[e] = b_c[e] = g_c[e] = c_c[e] = s_c[e] = 0;
+            a_v[e] = b_v[e] = g_v[e] = c_v[e] = s_v[e] = 0.f;
         }
-        int in_len = 0, hb_target = 0;
-        HEAD_ITERATIONS {
-            // 0. what this iteration needs of the rows of blocks i + 2, i - 1 and i + 1 (published at least one
+        int a_len = 0, b_len = 0, hb_target = 0;
+        auto iteration = [&](const int i, int (&ld_c)[ENT], float (&ld_v)[ENT], int &ld_len,
+                             const int (&ar_c)[ENT], const float (&ar_v)[ENT], const int ar_len) {
+            // 0. what this iteration needs of the rows of blocks i + 3, i - 1 and i + 1 (published at least one
             //    iteration ago) and the steps of block i - 1, read together: one trip to LDS instead of one per use
-            const bool has_in = i + 2 >= 0 && i + 2 < nb, has_s = i - 1 >= 0 && i - 1 < nb, has_g = i + 1 >= 0 && i + 1 < nb;
-            const RowSlot r_in = sh.rows[(i + 2) & (RING - 1)][rho];
+            const bool has_in = i + 3 >= 0 && i + 3 < nb, has_s = i - 1 >= 0 && i - 1 < nb, has_g = i + 1 >= 0 && i + 1 < nb;
+            const RowSlot r_in = sh.rows[(i + 3) & (RING - 1)][rho];
             const RowSlot r_s = sh.rows[(i - 1) & (RING - 1)][rho];
             const RowSlot r_g = sh.rows[(i + 1) & (RING - 1)][rho];
             const float dl = sh.delta[(i - 1) & 1][rho];
-            // 1. this lane's segment of the row of block i + 2 (unconditional vector loads)
+            // 1. this lane's segment of the row of block i + 3 (unconditional vector loads)
             if (has_in) {
                 const int32_t *cp = r_in.col + sub;
                 const float *vp = r_in.val + sub;
-                in_len = r_in.len;
+                ld_len = r_in.len;
 #pragma unroll
-                for (int e = 0; e < ENT; ++e) { in_c[e] = gld(cp + e * LPR); in_v[e] = gld(vp + e * LPR); }
+                for (int e = 0; e < ENT; ++e) { ld_c[e] = gld(cp + e * LPR); ld_v[e] = gld(vp + e * LPR); }
             } else {
-                in_len = 0;
+                ld_len = 0;
             }
             // 2. block i - 1 is added to the head of the private vector
             if (has_s && r_s.len > 0 && dl != 0.f) {
@@ -270,15 +288,11 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
             if (has_g) {
                 float got[ENT];
 #pragma unroll
-                for (int e = 0; e < ENT; ++e) {
-                    got[e] = 0.f;
-                    if (g_v[e] != 0.f) got[e] = (float)hot[g_c[e]];
-                }
+                for (int e = 0; e < ENT; ++e) got[e] = (float)hot[g_c[e]];   // (masked entries: column 0 times 0)
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < ENT; ++e) part += g_v[e] * got[e];
-#pragma unroll
-                for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o, 64);
+                part = sum_over_row_lanes(part);
                 if (sub == 0) {
                     if (A.n_tails > 0) {
                         wait_flag(&sh.xflag, i + 2);
@@ -301,17 +315,21 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
                     sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;
                 }
             }
-            // 5. move the entry sets one stage on; the incoming set is masked to the row's length and to the
-            //    head's columns
+            // 5. move the entry sets one stage on; the set that arrived (block i + 2) is masked to the row's
+            //    length and to the head's columns
 #pragma unroll
             for (int e = 0; e < ENT; ++e) {
                 s_c[e] = c_c[e]; s_v[e] = c_v[e];
                 c_c[e] = g_c[e]; c_v[e] = g_v[e];
-                const bool live = sub + e * LPR < in_len && in_c[e] < n_hot;
-                g_c[e] = live ? in_c[e] : 0;
-                g_v[e] = live ? in_v[e] : 0.f;
+                const bool live = sub + e * LPR < ar_len && ar_c[e] < n_hot;
+                g_c[e] = live ? ar_c[e] : 0;
+                g_v[e] = live ? ar_v[e] : 0.f;
             }
             __syncthreads();
+        };
+        for (int i = -6; i <= nb; i += 2) {          // HEAD_ITERATIONS, two at a time
+            iteration(i, a_c, a_v, a_len, b_c, b_v, b_len);
+            if (i + 1 <= nb) iteration(i + 1, b_c, b_v, b_len, a_c, a_v, a_len);
         }
     }
 #undef HEAD_ITERATIONS
@@ -482,8 +500,7 @@ __device__ __forceinline__ void split_tail(unsigned char *smem, const SplitArgs 
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < TE; ++e) part += st_v[0][e] * got[e];
-#pragma unroll
-                for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o, 64);
+                part = sum_over_row_lanes(part);
                 const int b = block_of(j);
                 if (sub == 0) ring_put(x_parts + (b & (SPLIT_RING - 1)) * BATCH + rho, part, b + 1);
             }

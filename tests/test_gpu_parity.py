@@ -199,6 +199,47 @@ def test_gram_tiles_match_their_definition(mods):
     g.close()
 
 
+def test_thinly_occupied_private_vectors(mods):
+    """Few rows over many columns: every solver touches a few of every hundred columns, the case in which the
+    merge picks a solver's entries straight from its compact vector (here with the solvers divided over
+    slices; the long-row benchmark size runs it unsliced)."""
+    oracle_mod, binding = mods
+    from workloads.generate import Problem
+    g = np.random.default_rng(11)
+    n, d, per_row, K = 600, 300000, 100, 4
+    col = np.sort(np.stack([g.choice(d, per_row, replace=False) for _ in range(n)]), axis=1).astype(np.int32).ravel()
+    val = (g.standard_normal(n * per_row) / np.sqrt(per_row)).astype(np.float32)
+    y = np.where(g.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    bounds = np.array(list(range(0, n, 128)) + [n], dtype=np.int64)
+    p = Problem("thin", "hinge", n, d, 1e-3, y, bounds, row_ptr=np.arange(n + 1, dtype=np.int64) * per_row, col=col, val=val)
+    cfg = dict(seed=4, rounds=4, schedule=[(0, K)], K=K, speeds=None)
+    print("\ncase thin n=%d d=%d K=%d" % (n, d, K), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, solver="auto", check_alpha_every=1, log=_log)
+
+
+@pytest.mark.parametrize("loss,l1", [("hinge", 0.0), ("squared", 0.0), ("logistic", 0.0), ("squared", 0.002)])
+def test_long_rows_over_a_shared_vector_of_many_slices(mods, loss, l1):
+    """Rows of hundreds of entries over two million columns: the gap's row pass cuts the shared vector into
+    slices (8 in float, 16 in double) and sums a row's dot product from its runs; rows of very different
+    lengths, an empty row, a ragged last chunk."""
+    oracle_mod, binding = mods
+    from workloads.generate import Problem
+    g = np.random.default_rng(17)
+    n, d, K = 330, 2_000_000, 3
+    lens = np.clip(np.round(g.lognormal(np.log(300), 0.7, n)), 1, 4000).astype(np.int64)
+    lens[5] = 0
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(lens, out=rp[1:])
+    col = np.concatenate([np.sort(g.choice(d, int(m), replace=False)) for m in lens]).astype(np.int32)
+    val = np.concatenate([g.choice([-1.0, 1.0], int(m)) / np.sqrt(max(int(m), 1)) for m in lens]).astype(np.float32)
+    y = np.where(g.random(n) < 0.5, 1.0, -1.0).astype(np.float32) if loss != "squared" else g.standard_normal(n).astype(np.float32)
+    bounds = np.array(list(range(0, n, 100)) + [n], dtype=np.int64)
+    p = Problem("slices", loss, n, d, 1e-3, y, bounds, row_ptr=rp, col=col, val=val)
+    cfg = dict(seed=6, rounds=4, schedule=[(0, K)], K=K)
+    print("\ncase slices %s l1=%g n=%d d=%d nnz=%d" % (loss, l1, n, d, rp[-1]), flush=True)
+    run_lockstep(cfg, p, oracle_mod, binding, solver="auto", check_alpha_every=1, log=_log, l1=l1)
+
+
 # ----------------------------------------------------------------------------- edges and contract
 def _tiny(binding, loss="hinge", dense=False, n=300, d=50, chunk=64, K=3, seed=5):
     g = np.random.default_rng(seed)
