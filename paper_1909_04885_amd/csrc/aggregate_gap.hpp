@@ -547,10 +547,16 @@ __global__ __launch_bounds__(256) void wsq_partial(const double *__restrict__ v,
 {
     double s = 0.0, t = 0.0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += stride) {
-        const double x = soft_threshold(v[j], l1);
-        s += x * x;
-        t += fabs(x);
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += 4 * stride) {
+        double x[4];                                 // four loads in flight per thread
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = j + q * stride < d ? v[j + q * stride] : 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const double y = soft_threshold(x[q], l1);
+            s += y * y;
+            t += fabs(y);
+        }
     }
     block_sum2_store(s, t, &part_wsq[blockIdx.x], &part_wabs[blockIdx.x]);
 }

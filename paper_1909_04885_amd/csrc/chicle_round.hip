@@ -324,6 +324,11 @@ int grid_for(int64_t items, int per_block, int cap)
     return (int)g;
 }
 
+void clear_device_words(chicle_ctx *c, void *p, int64_t n_words)
+{
+    hipLaunchKernelGGL(clear_words, dim3(grid_for(n_words, 256, 256)), dim3(256), 0, c->stream, (unsigned *)p, n_words);
+}
+
 int clear_all_private(chicle_ctx *c)
 {
     if (c->K <= 0) return CHICLE_OK;
@@ -417,7 +422,7 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
         if (c->long_rows && c->cluster > 1 && c->cluster_allowed) {
             // every solver shared by a cluster of workgroups on one L2 partition, each owning a range of columns
             const int k_pad = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
-            HIP_TRY(c, hipMemsetAsync(c->cluster_ring_dev, 0, sizeof(unsigned long long) * (size_t)CLUSTER_WORDS * (size_t)c->K, c->stream));
+            clear_device_words(c, c->cluster_ring_dev, 2 * (int64_t)CLUSTER_WORDS * c->K);
             hipLaunchKernelGGL((sdca_rowwise_csr_cluster<LOSS, 256, 2>), dim3(k_pad * c->cluster), dim3(256), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
                                perm, c->u, c->ld_v, ml, sc, c->err_dev, k_pad, c->cluster, c->row_split_dev,
@@ -498,7 +503,7 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, bool tiles_ready, const i
         const bool short_tail = c->compact && c->max_tail_entries <= 3 * LPR;
         auto kern = short_tail ? sdca_batched_split<LOSS, 3> : sdca_batched_split<LOSS, ENT>;
         HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
-        HIP_TRY(c, hipMemsetAsync(c->split_ring_dev, 0, sizeof(unsigned long long) * (size_t)SPLIT_WORDS * (size_t)c->K, c->stream));
+        clear_device_words(c, c->split_ring_dev, 2 * (int64_t)SPLIT_WORDS * c->K);
         seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
         hipLaunchKernelGGL(kern, dim3((1 + n_tails) * k_pad), dim3(SPLIT_THREADS), sh, c->stream, A, k_pad);
         seg_end(c, CHICLE_SEG_EPOCH_CHAIN);
@@ -506,7 +511,7 @@ int launch_batched(chicle_ctx *c, const int32_t *perm, bool tiles_ready, const i
         auto kern = sdca_batched_csr<LOSS>;
         HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
         const int first_warmer = k_pad;
-        HIP_TRY(c, hipMemsetAsync(c->progress_dev, 0, sizeof(int) * (size_t)c->K, c->stream));
+        clear_device_words(c, c->progress_dev, c->K);
         seg_begin(c, CHICLE_SEG_EPOCH_CHAIN);
         hipLaunchKernelGGL(kern, dim3(first_warmer + c->K), dim3(BATCHED_THREADS), sh, c->stream, c->chunks_dev,
                            c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev, perm, c->tiles[c->tile_buf], c->u,

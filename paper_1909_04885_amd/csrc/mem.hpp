@@ -29,4 +29,12 @@ __device__ __forceinline__ float ld_l2(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Zeroes n 32-bit words: the small buffers (rings, progress counters) that every local pass starts from zero
+// are cleared by a kernel and not by a memset node, so that a caller may capture a round in a HIP graph.
+__global__ __launch_bounds__(256) void clear_words(unsigned *p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
 }  // namespace chicle
