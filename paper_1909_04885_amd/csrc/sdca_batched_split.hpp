@@ -55,6 +55,53 @@ __device__ __forceinline__ float ring_get(const unsigned long long *p, int tag, 
     return __uint_as_float((unsigned)v);
 }
 
+// The wait of a polling wavefront (all 64 lanes, one ring word each), with several polls in flight: a poll is
+// a trip to L2 and back, so with one at a time an arrival is noticed a trip and a half later on average;
+// with POLL_DEPTH of them, issued a fraction of a trip apart, the one that sees it is already on its way.
+// PROGRESS: the same polls also fetch two progress words of the other tail, and the wait ends when the ring
+// words carry `tag` and those words have reached want_added / want_gathered.  Bounded like ring_get.
+constexpr int POLL_DEPTH = 1;
+template <bool PROGRESS>
+__device__ __forceinline__ float ring_wait(const unsigned long long *word, int tag, const unsigned long long *added,
+                                           int want_added, const unsigned long long *gathered, int want_gathered,
+                                           int *dead, int *err)
+{
+    unsigned long long v[POLL_DEPTH], a[POLL_DEPTH], g[POLL_DEPTH];
+#define RING_POLL(k)                                                                                        \
+    do {                                                                                                    \
+        v[k] = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);                         \
+        if (PROGRESS) {                                                                                     \
+            a[k] = __hip_atomic_load(added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);                    \
+            g[k] = __hip_atomic_load(gathered, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);                 \
+        }                                                                                                   \
+    } while (0)
+#pragma unroll
+    for (int k = 0; k < POLL_DEPTH; ++k) {
+        RING_POLL(k);
+        if (k + 1 < POLL_DEPTH) __builtin_amdgcn_s_sleep(2);
+    }
+    int spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int k = 0; k < POLL_DEPTH; ++k) {
+            bool ok = (int)(v[k] >> 32) == tag;
+            if (PROGRESS) ok = ok && (int)a[k] >= want_added && (int)g[k] >= want_gathered;
+            if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) return __uint_as_float((unsigned)v[k]);   // every lane's word is here
+            if (POLL_DEPTH == 1) __builtin_amdgcn_s_sleep(1);
+            RING_POLL(k);
+        }
+        spins += POLL_DEPTH;
+        if (spins > SPLIT_SPIN_LIMIT || __hip_atomic_load(dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
+            if (spins > SPLIT_SPIN_LIMIT) {
+                __hip_atomic_store(dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                atomicOr(err, ERR_PARTNER_TIMEOUT);
+            }
+            return 0.f;
+        }
+    }
+#undef RING_POLL
+}
+
 // Barrier among the helper wavefronts that orders their LDS traffic only (it does not wait for loads from
 // memory that are still in flight).
 __device__ __forceinline__ void helper_barrier_lds(int *cnt, int target)
@@ -203,8 +250,8 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
         HEAD_ITERATIONS {
             if (A.n_tails > 0 && i + 1 >= 0 && i + 1 < nb) {
                 const int t = (i + 1) % A.n_tails;                   // the tail that owns block i + 1
-                sh.xv[lane] = ring_get(x_parts + (t * SPLIT_RING + ((i + 1) & (SPLIT_RING - 1))) * BATCH + lane, i + 2,
-                                       &sh.dead, A.err);
+                sh.xv[lane] = ring_wait<false>(x_parts + (t * SPLIT_RING + ((i + 1) & (SPLIT_RING - 1))) * BATCH + lane, i + 2,
+                                               nullptr, 0, nullptr, 0, &sh.dead, A.err);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 if (lane == 0) __hip_atomic_store(&sh.xflag, i + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
@@ -390,24 +437,15 @@ __device__ __forceinline__ void split_tail(unsigned char *smem, const SplitArgs 
             const int ja = j - back;                                     // own block that is added this iteration
             if (ja >= 0 && ja < n_own) {
                 const int b = block_of(ja);
-                sh.xv[lane] = ring_get(x_steps + (b & (SPLIT_RING - 1)) * BATCH + lane, b + 1, &sh.dead, A.err);
-                // blocks before b that the other tail adds: all performed?  (b - 1 is its latest.)  And has it
-                // gathered block b + 1?
-                if (n_tails == 2 && lane == 0) {
-                    int spins = 0;
-                    while ((b >= 1 && (int)__hip_atomic_load(progress + (1 - tail), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < b) ||
-                           (b + 1 < nb && (int)__hip_atomic_load(progress + 2 + (1 - tail), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < b + 2)) {
-                        if (++spins > SPLIT_SPIN_LIMIT || __hip_atomic_load(&sh.dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
-                            if (spins > SPLIT_SPIN_LIMIT) {
-                                __hip_atomic_store(&sh.dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                                atomicOr(A.err, ERR_PARTNER_TIMEOUT);
-                            }
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                }
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                // the steps of block b; with two tails also: has the other tail performed every add before b
+                // (b - 1 is its latest), and has it gathered block b + 1?  All fetched by the same polls.
+                const unsigned long long *word = x_steps + (b & (SPLIT_RING - 1)) * BATCH + lane;
+                if (n_tails == 2)
+                    sh.xv[lane] = ring_wait<true>(word, b + 1, progress + (1 - tail), b, progress + 2 + (1 - tail),
+                                                  b + 1 < nb ? b + 2 : 0, &sh.dead, A.err);
+                else
+                    sh.xv[lane] = ring_wait<false>(word, b + 1, nullptr, 0, nullptr, 0, &sh.dead, A.err);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // (polls still in flight are not waited for)
                 if (lane == 0) __hip_atomic_store(&sh.xflag, ja + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             __syncthreads();
