@@ -35,31 +35,13 @@ __device__ __forceinline__ void ring_put(unsigned long long *p, float v, int tag
     const unsigned long long w = ((unsigned long long)(unsigned)tag << 32) | (unsigned long long)__float_as_uint(v);
     __hip_atomic_store(p, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// *dead (LDS) is set once any wait of the workgroup has given up; later waits return at once, so a lost
-// partner costs one time-out, not one per block.
-__device__ __forceinline__ float ring_get(const unsigned long long *p, int tag, int *dead, int *err)
-{
-    unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int spins = 0;
-    while ((int)(v >> 32) != tag) {
-        if (++spins > SPLIT_SPIN_LIMIT || __hip_atomic_load(dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
-            if (spins > SPLIT_SPIN_LIMIT) {
-                __hip_atomic_store(dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                atomicOr(err, ERR_PARTNER_TIMEOUT);
-            }
-            return 0.f;
-        }
-        __builtin_amdgcn_s_sleep(1);
-        v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    return __uint_as_float((unsigned)v);
-}
-
 // The wait of a polling wavefront (all 64 lanes, one ring word each), with several polls in flight: a poll is
 // a trip to L2 and back, so with one at a time an arrival is noticed a trip and a half later on average;
 // with POLL_DEPTH of them, issued a fraction of a trip apart, the one that sees it is already on its way.
 // PROGRESS: the same polls also fetch two progress words of the other tail, and the wait ends when the ring
-// words carry `tag` and those words have reached want_added / want_gathered.  Bounded like ring_get.
+// words carry `tag` and those words have reached want_added / want_gathered.  Bounded: after SPLIT_SPIN_LIMIT
+// polls the wait gives up, raises the error flag and sets *dead (LDS), which makes every later wait of the
+// workgroup return at once, so a lost partner costs one time-out, not one per block.
 constexpr int POLL_DEPTH = 1;
 template <bool PROGRESS>
 __device__ __forceinline__ float ring_wait(const unsigned long long *word, int tag, const unsigned long long *added,
