@@ -164,6 +164,7 @@ struct chicle_ctx {
     bool compact = false;
     int64_t words = 0;                // 32-column words per bitmap
     unsigned *bits_dev = nullptr;     // max_solvers x words: columns a solver's chunks contain
+    unsigned *multi_dev = nullptr;    // long rows: the same layout, columns that more than one row of the solver holds
     int32_t *pref_dev = nullptr;      // max_solvers x words: set bits before each word
     int32_t *count_dev = nullptr;     // max_solvers: columns per solver
     int64_t *u_off_dev = nullptr;     // max_solvers: start of each solver's compact vector in u
@@ -270,6 +271,7 @@ size_t fixed_bytes(int64_t n_total, int32_t d, int32_t n_chunks, int32_t max_sol
     if (compact) {
         const size_t words = ((size_t)d + 31) / 32;
         s += 2 * align_up(sizeof(int32_t) * words * (size_t)max_solvers);          // column bitmaps, prefix counts
+        if (long_rows) s += align_up(sizeof(int32_t) * words * (size_t)max_solvers);   // columns held by several rows
         s += align_up(sizeof(int32_t) * (size_t)max_solvers) + align_up(sizeof(int64_t) * (size_t)max_solvers);
         s += align_up(sizeof(int32_t) * (size_t)n_chunks);
     }
@@ -423,7 +425,7 @@ int launch_rowwise(chicle_ctx *c, const int32_t *perm)
             // every solver shared by a cluster of workgroups on one L2 partition, each owning a range of columns
             const int k_pad = (c->K + L2_PARTITIONS - 1) / L2_PARTITIONS * L2_PARTITIONS;
             clear_device_words(c, c->cluster_ring_dev, 2 * (int64_t)CLUSTER_WORDS * c->K);
-            hipLaunchKernelGGL((sdca_rowwise_csr_cluster<LOSS, 256, 2>), dim3(k_pad * c->cluster), dim3(256), sh, c->stream,
+            hipLaunchKernelGGL((sdca_rowwise_csr_cluster<LOSS, 512, 2>), dim3(k_pad * c->cluster), dim3(512), sh, c->stream,
                                c->chunks_dev, c->solvers_dev, c->solver_chunks_dev, c->solver_prefix_dev,
                                perm, c->u, c->ld_v, ml, sc, c->err_dev, k_pad, c->cluster, c->row_split_dev,
                                c->cluster_ring_dev, c->u_off_dev);
@@ -779,11 +781,12 @@ int chicle_create(chicle_ctx **out, int32_t loss, int64_t n_total, int32_t d, do
         c->words = ((int64_t)d + 31) / 32;
         c->bits_dev = (unsigned *)carve(c, sizeof(unsigned) * (size_t)c->words * (size_t)max_solvers);
         c->pref_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)c->words * (size_t)max_solvers);
+        if (c->long_rows) c->multi_dev = (unsigned *)carve(c, sizeof(unsigned) * (size_t)c->words * (size_t)max_solvers);
         c->count_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)max_solvers);
         c->u_off_dev = (int64_t *)carve(c, sizeof(int64_t) * (size_t)max_solvers);
         c->chunk_owner_dev = (int32_t *)carve(c, sizeof(int32_t) * (size_t)n_chunks);
     }
-    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || !c->split_ring_dev || (c->long_rows && (!c->cluster_ring_dev || !c->slice_z_dev)) || (c->compact && !c->chunk_owner_dev)) { delete c; return CHICLE_ENOMEM; }
+    if (!c->err_dev || !c->ticks_dev || !c->progress_dev || !c->split_ring_dev || (c->long_rows && (!c->cluster_ring_dev || !c->slice_z_dev)) || (c->compact && (!c->chunk_owner_dev || (c->long_rows && !c->multi_dev)))) { delete c; return CHICLE_ENOMEM; }
 
     c->chunks.assign(n_chunks, ChunkDev{});
     c->loaded.assign(n_chunks, 0);
@@ -1062,7 +1065,8 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
         const dim3 egrid(grid_for(max_nnz, 256, 1024), c->n_chunks);
         HIP_TRY(c, hipMemcpyAsync(c->chunk_owner_dev, chunk_to_solver, sizeof(int32_t) * (size_t)c->n_chunks, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemsetAsync(c->bits_dev, 0, sizeof(unsigned) * (size_t)c->words * (size_t)K, c->stream));
-        hipLaunchKernelGGL(mark_columns, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev, c->words);
+        if (c->multi_dev) HIP_TRY(c, hipMemsetAsync(c->multi_dev, 0, sizeof(unsigned) * (size_t)c->words * (size_t)K, c->stream));
+        hipLaunchKernelGGL(mark_columns, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev, c->words, c->multi_dev);
         const int forced = batched_eligible(c) ? batched_layout(c).n_hot : 0;
         if (forced > 0)
             hipLaunchKernelGGL(force_columns, dim3(K), dim3(256), 0, c->stream, c->bits_dev, c->words, forced);
@@ -1078,7 +1082,7 @@ int chicle_assign(chicle_ctx *c, int32_t K, const int32_t *chunk_to_solver)
         c->u_used = used;
         HIP_TRY(c, hipMemcpyAsync(c->u_off_dev, off.data(), sizeof(int64_t) * (size_t)K, hipMemcpyHostToDevice, c->stream));
         hipLaunchKernelGGL(compact_indices, egrid, dim3(256), 0, c->stream, c->chunks_dev, c->chunk_owner_dev, c->bits_dev,
-                           c->pref_dev, c->words);
+                           c->pref_dev, c->words, (const unsigned *)c->multi_dev);
         HIP_TRY(c, hipGetLastError());
         if (forced > 0) {
             int max_rows = 1;

@@ -49,14 +49,19 @@ __global__ __launch_bounds__(256) void renumber_rows(const ChunkDev *__restrict_
 // of that solver's compact vector.
 
 // bits[owner[chunk]][c >> 5] |= 1 << (c & 31) for every entry.  Grid: (blocks over entries, chunk).
+// multi (may be null): the same layout, a bit is set when a second entry of the solver's chunks holds the column
+// (the columns inside a row are distinct, so that is another row).
 __global__ __launch_bounds__(256) void mark_columns(const ChunkDev *__restrict__ chunks, const int32_t *__restrict__ owner,
-                                                    unsigned *bits, int64_t words)
+                                                    unsigned *bits, int64_t words, unsigned *multi)
 {
     const ChunkDev &ch = chunks[blockIdx.y];
     unsigned *mine = bits + (int64_t)owner[blockIdx.y] * words;
+    unsigned *more = multi ? multi + (int64_t)owner[blockIdx.y] * words : nullptr;
     for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < ch.nnz; p += (int64_t)gridDim.x * 256) {
         const int c = ch.col[p];
-        atomicOr(mine + (c >> 5), 1u << (c & 31));
+        const unsigned bit = 1u << (c & 31);
+        const unsigned old = atomicOr(mine + (c >> 5), bit);
+        if (more && (old & bit)) atomicOr(more + (c >> 5), bit);
     }
 }
 
@@ -102,9 +107,11 @@ __global__ __launch_bounds__(1024) void prefix_columns(const unsigned *__restric
 }
 
 // The compact index of every entry, written behind the chunk's column ids.  Grid: (blocks over entries, chunk).
+// multi (may be null): see mark_columns; an entry whose column no other row of the solver holds gets the sign
+// bit (UNIQUE_COLUMN in mem.hpp).
 __global__ __launch_bounds__(256) void compact_indices(const ChunkDev *__restrict__ chunks, const int32_t *__restrict__ owner,
                                                        const unsigned *__restrict__ bits, const int32_t *__restrict__ pref,
-                                                       int64_t words)
+                                                       int64_t words, const unsigned *__restrict__ multi)
 {
     const ChunkDev &ch = chunks[blockIdx.y];
     const int64_t k = owner[blockIdx.y];
@@ -117,6 +124,7 @@ __global__ __launch_bounds__(256) void compact_indices(const ChunkDev *__restric
         if (p < ch.nnz) {
             const int c = ch.col[p];
             idx = pf[c >> 5] + __popc(b[c >> 5] & ((1u << (c & 31)) - 1u));
+            if (multi && !(multi[k * words + (c >> 5)] & (1u << (c & 31)))) idx |= (int)0x80000000;
         }
         out[p] = idx;
     }

@@ -29,6 +29,19 @@ __device__ __forceinline__ float ld_l2(const float *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Index of an entry in its solver's compact private vector, with the sign bit set where no other row of the
+// solver holds that column (long-row contexts): the gather of such an entry is known to be zero (the vector is
+// zero at the start of a pass and nothing else writes there) and its update is a plain store, not a
+// read-modify-write that fetches a whole line for four bytes.
+constexpr int UNIQUE_COLUMN = (int)0x80000000;
+__device__ __forceinline__ int vec_index(int c) { return c & 0x7fffffff; }
+__device__ __forceinline__ float gather_entry(const float *u, int c) { return c < 0 ? 0.f : ld_l2(u + c); }
+__device__ __forceinline__ void add_entry(float *u, int c, float x)
+{
+    if (c < 0) gst(u + vec_index(c), x);
+    else unsafeAtomicAdd(u + c, x);
+}
+
 // Zeroes n 32-bit words: the small buffers (rings, progress counters) that every local pass starts from zero
 // are cleared by a kernel and not by a memset node, so that a caller may capture a round in a HIP graph.
 __global__ __launch_bounds__(256) void clear_words(unsigned *p, int64_t n)

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             got[e] = 0.f;
-            if (step && tid + e * BLOCK < m.len) got[e] = ld_l2(u + c_c[e]);
+            if (step && tid + e * BLOCK < m.len) got[e] = gather_entry(u, c_c[e]);
         }
         if (t + 1 >= 0 && t + 1 < n) {
             const RowMeta &mn = ring[(t + 1) & 3];
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
                 float part = 0.f;
 #pragma unroll
                 for (int e = 0; e < EPT; ++e) part += c_v[e] * got[e];
-                for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK) part += gld(m.val + p) * ld_l2(u + gld(m.col + p));
+                for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK) part += gld(m.val + p) * gather_entry(u, gld(m.col + p));
                 const float xu = block_sum<BLOCK>(part, red);
                 const float delta = dual_step<LOSS>(m.alpha, m.y, m.rw, xu, m.q, sc.c);
                 if (tid == 0) {
@@ -261,9 +261,9 @@ __global__ __launch_bounds__(BLOCK) void sdca_rowwise_csr(
                 if (coef != 0.0f) {
 #pragma unroll
                     for (int e = 0; e < EPT; ++e)
-                        if (tid + e * BLOCK < m.len) unsafeAtomicAdd(u + c_c[e], coef * c_v[e]);
+                        if (tid + e * BLOCK < m.len) add_entry(u, c_c[e], coef * c_v[e]);
                     for (int p = tid + EPT * BLOCK; p < m.len; p += BLOCK)
-                        unsafeAtomicAdd(u + gld(m.col + p), coef * gld(m.val + p));
+                        add_entry(u, gld(m.col + p), coef * gld(m.val + p));
                 }
             }
         }
