@@ -110,6 +110,48 @@ def cpu_baseline(p, cfg, table, K, budget_s=15.0):
             "sample": "%d whole rounds of the same workload (local pass + aggregate + gap), %.1f s" % (rounds, spent)}
 
 
+def elastic_schedule(chicle, p, cfg, round_permutations):
+    """The configured (round, K) schedule with unequal solver speeds (Section 5.4: uni-tasks on nodes of
+    different speed get data in proportion to their speed): per phase the measured time of a round, the time
+    of the reassignment, and the projected iteration time of the greedy assignment, max_k load_k / speed_k,
+    against a perfect split (total load / total speed).  The GPU runs every solver at full speed: the speeds
+    only weight the assignment, so the measured time is that of the unbalanced table."""
+    import torch
+    from workloads.configs import k_for_round, speeds_for
+    loads = p.chunk_nnz()
+    g = chicle.ChicleRound.from_problem(p, max_solvers=max(k for _, k in cfg["schedule"]))
+    phases, K, rows = [], None, None
+    for r in range(cfg["rounds"]):
+        Kr = k_for_round(cfg, r)
+        if Kr != K:
+            K = Kr
+            sp = speeds_for(cfg, K)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            table = chicle.balance(loads, K, sp)
+            g.assign(K, table)
+            g.sync()
+            assign_ms = (time.perf_counter() - t0) * 1e3
+            rows = g.solver_rows()
+            speed = np.array([1.0] * K if sp is None else [q / max(sp) for q in sp])
+            per_solver = np.bincount(table, weights=loads, minlength=K)
+            phases.append({"first_round": r, "K": K, "assign_ms": assign_ms, "round_ms": [],
+                           "projected_iteration_load": float(np.max(per_solver / speed)),
+                           "perfect_split_load": float(loads.sum() / speed.sum())})
+        perm = g.upload_perm(round_permutations(cfg["seed"], r, rows))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.local_epoch(perm); g.aggregate(); gap = g.gap()[2]
+        phases[-1]["round_ms"].append((time.perf_counter() - t0) * 1e3)
+        phases[-1]["gap_after"] = gap
+    g.close()
+    for ph in phases:
+        ph["rounds"] = len(ph["round_ms"])
+        ph["round_ms_median"] = float(np.median(ph.pop("round_ms")))
+        ph["imbalance"] = ph["projected_iteration_load"] / ph["perfect_split_load"]
+    return phases
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -268,6 +310,8 @@ def main():
                 "rule": dict(rule, K_start=args.scale_in_from), "rounds": res["rounds_to_target"],
                 "ms": None if res["seconds_to_target"] is None else 1e3 * res["seconds_to_target"],
                 "solvers_per_round": res["K_per_round"][:res["rounds_to_target"] or None]}
+    if len(cfg["schedule"]) > 1:
+        out["elastic_schedule"] = elastic_schedule(chicle, p, cfg, round_permutations)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(p, cfg, table, K)
     print(json.dumps(out), flush=True)
