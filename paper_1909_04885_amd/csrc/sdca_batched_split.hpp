@@ -323,25 +323,32 @@ __device__ __forceinline__ void split_head(unsigned char *smem, const SplitArgs 
                 for (int e = 0; e < ENT; ++e) part += g_v[e] * got[e];
                 part = sum_over_row_lanes(part);
                 if (sub == 0) {
+                    // everything that does not need the tails' share is done before it is waited for: what follows
+                    // the wait is on the path between the workgroups
+                    const int ring = (i + 1) & (RING - 1);
+                    const bool live = r_g.len > 0;
+                    float scale = 0.f, lo = 0.f, hi = 0.f;
+                    if (live && LOSS == 0) { scale = sc.c / r_g.q; lo = -r_g.alpha; hi = 1.f - r_g.alpha; }
+                    if (live && LOSS == 1) scale = sc.c / (sc.c + r_g.q);
+                    if (LOSS != 2) { sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi; }
                     if (A.n_tails > 0) {
                         wait_flag(&sh.xflag, i + 2);
-                        part += sh.xv[rho];                               // the tail's share of x_i . u
+                        part += sh.xv[rho];                               // the tails' share of x_i . u
                     }
-                    const int ring = (i + 1) & (RING - 1);
-                    float t0 = 0.f, lo = 0.f, hi = 0.f;
-                    if (r_g.len > 0) {
+                    float t0 = 0.f;
+                    if (live) {
                         if (LOSS == 0) {
-                            t0 = (sc.c / r_g.q) * (r_g.rw - r_g.y * part);
-                            lo = -r_g.alpha; hi = 1.f - r_g.alpha;
+                            t0 = scale * (r_g.rw - r_g.y * part);
                         } else if (LOSS == 1) {
-                            t0 = (sc.c / (sc.c + r_g.q)) * (r_g.rw - r_g.alpha - part);
+                            t0 = scale * (r_g.rw - r_g.alpha - part);
                         } else {
                             t0 = r_g.rw - r_g.y * part;
                             const float rr = r_g.q * sc.inv_c;
                             logistic_step(t0, rr, r_g.alpha, t0 + rr * (r_g.alpha - 0.5f), &lo);   // lo: the root for t0
                         }
                     }
-                    sh.t0[ring][rho] = t0; sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi;
+                    sh.t0[ring][rho] = t0;
+                    if (LOSS == 2) { sh.lo[ring][rho] = lo; sh.hi[ring][rho] = hi; }
                 }
             }
             // 5. move the entry sets one stage on; the set that arrived (block i + 2) is masked to the row's
