@@ -91,6 +91,18 @@ def test_full_sparse_zipf(mods, name):
     run_lockstep(cfg, p, oracle_mod, binding, sample_solvers=[0, 3, 7, 31], log=_log, ahead=True)
 
 
+def test_full_sparse_zipf_elastic_net(mods):
+    """The benchmark's sizes with the L1 term (over a third of the shared vector at exactly zero after five rounds):
+    compact merge in solver slices, gap with the L1 term, tiles prepared ahead."""
+    oracle_mod, binding = mods
+    cfg, p = cached_problem("sparse_zipf", "full")
+    print("\ncase sparse_zipf full l1=0.005 n=%d d=%d nnz=%d" % (p.n, p.d, p.nnz), flush=True)
+    rec = run_lockstep(cfg, p, oracle_mod, binding, rounds=5, sample_solvers=[0, 13, 31], log=_log, ahead=True, l1=0.005)
+    assert 0.05 < rec[-1]["w_zero"] < 0.95
+    for r in rec:
+        assert abs(r["P_gpu"] - r["P_ref"]) <= 1e-5 * abs(r["P_ref"]) + 1e-7
+
+
 def test_full_sparse_longrow(mods):
     oracle_mod, binding = mods
     cfg, p = cached_problem("sparse_longrow", "full")
